@@ -1,0 +1,187 @@
+"""fp64 CPU oracle for the tree-verification step -- TEST INFRASTRUCTURE.
+
+Thin ctypes/numpy front end of ``specvlm_oracle.c`` (same directory), which
+holds the plain definitions (SpecVLM Sec. 3.1 verification, Sec. 4.1 tree
+attention).  Only ``tests/``, the smoke check and the benchmark's
+``cpu_baseline`` leg may import this package; the product path never does.
+It shares no code with the HIP library.
+
+bf16 tensors are passed as ``uint16`` bit patterns, fp32 as ``float32``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "specvlm_oracle.c")
+_LIB = os.path.join(_HERE, "libspecvlm_oracle.so")
+_lib = None
+
+BF16, F32 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (OpenMP over heads/nodes only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.uint16:
+        return BF16
+    if a.dtype == np.float32:
+        return F32
+    raise TypeError(f"oracle takes uint16 (bf16 bits) or float32, got {a.dtype}")
+
+
+def _estrides(a: np.ndarray):
+    return [s // a.itemsize for s in a.strides]
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def ancestors(parent):
+    """(anc [n,n] uint8, depth [n] int32) of one parent array."""
+    parent = _i32(parent)
+    n = parent.shape[0]
+    anc = np.zeros((n, n), dtype=np.uint8)
+    depth = np.zeros(n, dtype=np.int32)
+    rc = _load().oracle_ancestors(ctypes.c_int(n), _p(parent), _p(anc), _p(depth))
+    if rc:
+        raise ValueError("parent array is not a topologically ordered tree")
+    return anc, depth
+
+
+def tree_attn(q, k, v, prefix_len, parent, num_nodes=None, *, scale=None,
+              block_table=None, block_size=16):
+    """Tree-masked attention by definition.
+
+    q [B,N_max,Hq,D]; contiguous cache k,v [B,Hkv,S_cap,D], or paged
+    [num_blocks,Hkv,block_size,D] with block_table [B,max_blocks].
+    Returns (o [B,N_max,Hq,D] float64, lse [B,Hq,N_max] float64).
+    """
+    dt = _dtype_code(q)
+    assert _dtype_code(k) == dt and _dtype_code(v) == dt
+    B, N_max, Hq, D = q.shape
+    Hkv = k.shape[1]
+    assert q.strides[3] == q.itemsize and k.strides[3] == k.itemsize
+    assert k.shape == v.shape and k.strides == v.strides
+    qs = _estrides(q)
+    ks = _estrides(k)
+    prefix_len = _i32(prefix_len)
+    parent = _i32(parent).reshape(B, N_max)
+    nn = None if num_nodes is None else _i32(num_nodes)
+    bt = None
+    max_blocks = 0
+    if block_table is not None:
+        bt = _i32(block_table)
+        max_blocks = bt.shape[1]
+        assert k.shape[2] == block_size
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    o = np.zeros((B, N_max, Hq, D), dtype=np.float64)
+    lse = np.zeros((B, Hq, N_max), dtype=np.float64)
+    I64 = ctypes.c_int64
+    rc = _load().oracle_tree_attn(
+        ctypes.c_int(dt), ctypes.c_int(B), ctypes.c_int(Hq), ctypes.c_int(Hkv),
+        ctypes.c_int(D), ctypes.c_int(N_max), ctypes.c_double(scale),
+        _p(q), I64(qs[0]), I64(qs[1]), I64(qs[2]),
+        _p(k), _p(v), I64(ks[0]), I64(ks[1]), I64(ks[2]),
+        _p(bt), ctypes.c_int(block_size), ctypes.c_int(max_blocks),
+        _p(prefix_len), _p(nn), _p(parent), _p(o), _p(lse))
+    if rc:
+        raise ValueError(f"oracle_tree_attn failed with status {rc}")
+    return o, lse
+
+
+def node_argmax(logits, num_nodes=None):
+    """logits [B,N_max,V] (uint16 bf16 bits or float32) -> amax [B,N_max] int32."""
+    dt = _dtype_code(logits)
+    B, N_max, V = logits.shape
+    assert logits.strides[2] == logits.itemsize
+    st = _estrides(logits)
+    nn = None if num_nodes is None else _i32(num_nodes)
+    amax = np.zeros((B, N_max), dtype=np.int32)
+    _load().oracle_node_argmax(
+        ctypes.c_int(dt), ctypes.c_int(B), ctypes.c_int(N_max), ctypes.c_int(V),
+        _p(logits), ctypes.c_int64(st[0]), ctypes.c_int64(st[1]), _p(nn), _p(amax))
+    return amax
+
+
+def tree_accept(parent, draft_tok, amax, num_nodes=None, path_cap=8):
+    """Returns (accept_len [B], path [B,path_cap], bonus_tok [B], committed_tok [B,path_cap])."""
+    parent = _i32(parent)
+    B, N_max = parent.shape
+    draft_tok = _i32(draft_tok).reshape(B, N_max)
+    amax = _i32(amax).reshape(B, N_max)
+    nn = None if num_nodes is None else _i32(num_nodes)
+    accept_len = np.zeros(B, dtype=np.int32)
+    path = np.zeros((B, path_cap), dtype=np.int32)
+    bonus = np.zeros(B, dtype=np.int32)
+    committed = np.zeros((B, path_cap), dtype=np.int32)
+    rc = _load().oracle_tree_accept(
+        ctypes.c_int(B), ctypes.c_int(N_max), ctypes.c_int(path_cap),
+        _p(parent), _p(draft_tok), _p(amax), _p(nn),
+        _p(accept_len), _p(path), _p(bonus), _p(committed))
+    if rc:
+        raise ValueError(f"oracle_tree_accept failed with status {rc}")
+    return accept_len, path, bonus, committed
+
+
+def kv_compact(k, v, prefix_len, path, accept_len, *, block_table=None, block_size=16):
+    """In-place compaction of k, v [L, ...cache dims...] (see tree_attn for the
+    per-layer layouts).  Returns (new_prefix_len [B], moved_idx [B,path_cap,2])."""
+    assert k.dtype == v.dtype and k.shape == v.shape and k.strides == v.strides
+    assert k.flags.writeable and v.flags.writeable
+    L = k.shape[0]
+    Hkv, D = k.shape[2], k.shape[4]
+    st = _estrides(k)
+    prefix_len = _i32(prefix_len)
+    B = prefix_len.shape[0]
+    path = _i32(path).reshape(B, -1)
+    path_cap = path.shape[1]
+    accept_len = _i32(accept_len)
+    bt = None
+    max_blocks = 0
+    if block_table is not None:
+        bt = _i32(block_table)
+        max_blocks = bt.shape[1]
+    new_prefix = np.zeros(B, dtype=np.int32)
+    moved = np.zeros((B, path_cap, 2), dtype=np.int32)
+    I64 = ctypes.c_int64
+    rc = _load().oracle_kv_compact(
+        ctypes.c_int(L), ctypes.c_int(B), ctypes.c_int(Hkv), ctypes.c_int(D),
+        ctypes.c_int(k.itemsize), _p(k), _p(v), I64(st[0]),
+        I64(st[1]), I64(st[2]), I64(st[3]),
+        _p(bt), ctypes.c_int(block_size), ctypes.c_int(max_blocks),
+        _p(prefix_len), _p(path), ctypes.c_int(path_cap), _p(accept_len),
+        _p(new_prefix), _p(moved))
+    if rc:
+        raise ValueError(f"oracle_kv_compact failed with status {rc}")
+    return new_prefix, moved

@@ -1,0 +1,325 @@
+/*
+ * specvlm_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * Plain, slow, fp64 CPU definition of the target model's verification step
+ * over a draft token tree (SpecVLM, Sec. 3.1: the target "verifies" the
+ * drafted tokens in one forward pass and the incorrect ones are discarded;
+ * Sec. 4.1: the draft is an EAGLE-2 style token tree, Top-K 10, 60 tokens,
+ * depth 7).  The paper never writes these steps as formulas, so every
+ * function below is the plain mathematical definition of what that sentence
+ * requires, written out without blocking, fusion or reordering:
+ *
+ *   oracle_ancestors      ancestor-or-self sets of a parent array
+ *   oracle_tree_attn      softmax attention where tree node i sees the whole
+ *                         committed prefix plus its own ancestors-or-self
+ *   oracle_node_argmax    greedy (temperature 0) target token per node,
+ *                         lowest index on ties
+ *   oracle_tree_accept    longest root path whose drafted tokens equal the
+ *                         target's greedy tokens ("lossless" verification)
+ *   oracle_kv_compact     move the accepted path's K/V rows to the front of
+ *                         the tree region (read-all-then-write)
+ *
+ * Pinned by tests/test_oracle_*.py against: textbook causal attention (chain
+ * tree), plain decode attention (one node), a numpy brute force with a
+ * materialised mask, hand-worked fixtures under tests/golden/, the closed form
+ * sigma = alpha(1-alpha^gamma)/(1-alpha) of Sec. 3.1, and exhaustive path
+ * enumeration on tiny trees.
+ *
+ * Only tests/, the smoke check and the benchmark's cpu_baseline leg may call
+ * this file.  It shares no code with the HIP library.
+ *
+ * Element types: dtype 0 = bf16 stored as uint16 bit patterns, dtype 1 =
+ * IEEE fp32.  Both convert to double exactly, so the oracle sees exactly the
+ * bits the GPU sees.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static double elem_as_double(const void *base, int dtype, int64_t idx)
+{
+    if (dtype == 1)
+        return (double)((const float *)base)[idx];
+    uint32_t w = (uint32_t)((const uint16_t *)base)[idx] << 16;
+    float f;
+    memcpy(&f, &w, sizeof f);
+    return (double)f;
+}
+
+/* Number of threads an OpenMP parallel region will use here (1 without OpenMP). */
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/*
+ * Ancestor-or-self sets.  parent[0] = -1 (root), 0 <= parent[i] < i otherwise.
+ * anc[i*n + j] = 1 iff j is i or an ancestor of i.  depth[i] = edges from root.
+ * Returns 0, or 1 when the parent array is not a topologically ordered tree.
+ */
+int oracle_ancestors(int n, const int32_t *parent, uint8_t *anc, int32_t *depth)
+{
+    if (n < 1 || parent[0] != -1)
+        return 1;
+    for (int i = 1; i < n; ++i)
+        if (parent[i] < 0 || parent[i] >= i)
+            return 1;
+    memset(anc, 0, (size_t)n * (size_t)n);
+    for (int i = 0; i < n; ++i) {
+        int d = 0;
+        for (int t = i; t != -1; t = parent[t]) {
+            anc[(size_t)i * n + t] = 1;
+            if (t != i)
+                ++d;
+        }
+        depth[i] = d;
+    }
+    return 0;
+}
+
+/* Logical cache slot -> element offset of that token's row for KV head hk. */
+static int64_t kv_row_offset(int b, int hk, int slot,
+                             int64_t kv_sb, int64_t kv_sh, int64_t kv_st,
+                             const int32_t *block_table, int block_size, int max_blocks)
+{
+    if (block_table) {
+        int blk = block_table[(int64_t)b * max_blocks + slot / block_size];
+        return (int64_t)blk * kv_sb + (int64_t)hk * kv_sh + (int64_t)(slot % block_size) * kv_st;
+    }
+    return (int64_t)b * kv_sb + (int64_t)hk * kv_sh + (int64_t)slot * kv_st;
+}
+
+/*
+ * Tree-masked attention (definition).  For request b, query head h, tree node
+ * i < num_nodes[b]:
+ *     J(i) = {0..P_b-1}  U  {P_b + j : j ancestor-or-self of i}
+ *     s_j  = scale * sum_d q[b,i,h,d] * K[b,kv(h),j,d]          kv(h) = h / (Hq/Hkv)
+ *     o    = sum_J exp(s_j - M) V_j / sum_J exp(s_j - M),        M = max_J s_j
+ *     lse  = M + ln sum_J exp(s_j - M)
+ * q is [B,N_max,Hq,D] through element strides (q_sb,q_sn,q_sh); K/V are either
+ * contiguous (block_table NULL: kv_sb is the request stride) or paged
+ * (kv_sb is the block stride).  Outputs: o [B,N_max,Hq,D] dense doubles,
+ * lse [B,Hq,N_max] doubles (may be NULL).  Rows i >= num_nodes[b] are set to 0.
+ * num_nodes NULL means every request has N_max nodes.
+ * Returns 0, 1 on a malformed tree, 2 on allocation failure.
+ */
+int oracle_tree_attn(int dtype, int B, int Hq, int Hkv, int D, int N_max, double scale,
+                     const void *q, int64_t q_sb, int64_t q_sn, int64_t q_sh,
+                     const void *k, const void *v,
+                     int64_t kv_sb, int64_t kv_sh, int64_t kv_st,
+                     const int32_t *block_table, int block_size, int max_blocks,
+                     const int32_t *prefix_len, const int32_t *num_nodes,
+                     const int32_t *parent, double *o, double *lse)
+{
+    int status = 0;
+    int group = Hq / Hkv;
+    for (int b = 0; b < B; ++b) {
+        int n = num_nodes ? num_nodes[b] : N_max;
+        int P = prefix_len[b];
+        uint8_t *anc = malloc((size_t)n * n);
+        int32_t *depth = malloc(sizeof(int32_t) * n);
+        if (!anc || !depth) {
+            free(anc); free(depth);
+            return 2;
+        }
+        if (oracle_ancestors(n, parent + (int64_t)b * N_max, anc, depth)) {
+            free(anc); free(depth);
+            return 1;
+        }
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int h = 0; h < Hq; ++h) {
+            int hk = h / group;
+            int S = P + n;
+            double *s = malloc(sizeof(double) * S);
+            double *acc = malloc(sizeof(double) * D);
+            if (!s || !acc) {
+#pragma omp atomic write
+                status = 2;
+                free(s); free(acc);
+                continue;
+            }
+            for (int i = 0; i < N_max; ++i) {
+                double *orow = o + (((int64_t)b * N_max + i) * Hq + h) * D;
+                if (i >= n) {
+                    for (int d = 0; d < D; ++d) orow[d] = 0.0;
+                    if (lse) lse[((int64_t)b * Hq + h) * N_max + i] = 0.0;
+                    continue;
+                }
+                int64_t qoff = (int64_t)b * q_sb + (int64_t)i * q_sn + (int64_t)h * q_sh;
+                /* scores over the visible set, maximum */
+                double M = -INFINITY;
+                for (int j = 0; j < S; ++j) {
+                    int visible = (j < P) || anc[(size_t)i * n + (j - P)];
+                    if (!visible) { s[j] = -INFINITY; continue; }
+                    int64_t koff = kv_row_offset(b, hk, j, kv_sb, kv_sh, kv_st,
+                                                 block_table, block_size, max_blocks);
+                    double dot = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        dot += elem_as_double(q, dtype, qoff + d) * elem_as_double(k, dtype, koff + d);
+                    s[j] = scale * dot;
+                    if (s[j] > M) M = s[j];
+                }
+                /* softmax-weighted sum of V rows */
+                double Z = 0.0;
+                for (int d = 0; d < D; ++d) acc[d] = 0.0;
+                for (int j = 0; j < S; ++j) {
+                    int visible = (j < P) || anc[(size_t)i * n + (j - P)];
+                    if (!visible) continue;
+                    double w = exp(s[j] - M);
+                    Z += w;
+                    int64_t voff = kv_row_offset(b, hk, j, kv_sb, kv_sh, kv_st,
+                                                 block_table, block_size, max_blocks);
+                    for (int d = 0; d < D; ++d)
+                        acc[d] += w * elem_as_double(v, dtype, voff + d);
+                }
+                for (int d = 0; d < D; ++d) orow[d] = acc[d] / Z;
+                if (lse) lse[((int64_t)b * Hq + h) * N_max + i] = M + log(Z);
+            }
+            free(s); free(acc);
+        }
+        free(anc); free(depth);
+        if (status) return status;
+    }
+    return status;
+}
+
+/*
+ * Greedy target token per node (temperature 0):
+ *     amax[b,i] = min { v : logits[b,i,v] = max_v' logits[b,i,v'] }
+ * Values compare as real numbers (so -0 equals +0).  Precondition: no NaN.
+ * An all -inf row gives index 0.  Rows i >= num_nodes[b] give -1.
+ * logits are addressed as b*stride_b + i*stride_n + v (elements).
+ */
+int oracle_node_argmax(int dtype, int B, int N_max, int V, const void *logits,
+                       int64_t stride_b, int64_t stride_n,
+                       const int32_t *num_nodes, int32_t *amax)
+{
+#pragma omp parallel for collapse(2)
+    for (int b = 0; b < B; ++b) {
+        for (int i = 0; i < N_max; ++i) {
+            int n = num_nodes ? num_nodes[b] : N_max;
+            if (i >= n) { amax[(int64_t)b * N_max + i] = -1; continue; }
+            int64_t off = (int64_t)b * stride_b + (int64_t)i * stride_n;
+            int best = 0;
+            double bestv = elem_as_double(logits, dtype, off);
+            for (int v = 1; v < V; ++v) {
+                double x = elem_as_double(logits, dtype, off + v);
+                if (x > bestv) { bestv = x; best = v; }
+            }
+            amax[(int64_t)b * N_max + i] = best;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Greedy acceptance walk.  Node 0 is the root (a token the target already
+ * committed; Fig. 3: the target's first token initialises the tree); its draft
+ * token is not matched.  For i >= 1:
+ *     match(i) = draft_tok[i] == amax[parent[i]]
+ *     ok(0) = true, ok(i) = ok(parent[i]) and match(i)
+ *     best = the ok node of greatest depth, lowest node index on ties
+ * path = root..best = a_0..a_m (padded with -1 up to path_cap),
+ * accept_len = m, bonus_tok = amax[best],
+ * committed_tok = draft_tok[a_1..a_m] then bonus_tok (padded with -1).
+ * Returns 0, 1 on a malformed tree, 3 if a path would not fit in path_cap.
+ */
+int oracle_tree_accept(int B, int N_max, int path_cap,
+                       const int32_t *parent, const int32_t *draft_tok, const int32_t *amax,
+                       const int32_t *num_nodes,
+                       int32_t *accept_len, int32_t *path, int32_t *bonus_tok,
+                       int32_t *committed_tok)
+{
+    for (int b = 0; b < B; ++b) {
+        int n = num_nodes ? num_nodes[b] : N_max;
+        const int32_t *par = parent + (int64_t)b * N_max;
+        const int32_t *tok = draft_tok + (int64_t)b * N_max;
+        const int32_t *am = amax + (int64_t)b * N_max;
+        if (n < 1 || par[0] != -1) return 1;
+        int *ok = malloc(sizeof(int) * n);
+        int *depth = malloc(sizeof(int) * n);
+        ok[0] = 1; depth[0] = 0;
+        int best = 0;
+        for (int i = 1; i < n; ++i) {
+            if (par[i] < 0 || par[i] >= i) { free(ok); free(depth); return 1; }
+            depth[i] = depth[par[i]] + 1;
+            ok[i] = ok[par[i]] && (tok[i] == am[par[i]]);
+            if (ok[i] && depth[i] > depth[best]) best = i;   /* strict: ties keep the lower index */
+        }
+        int m = depth[best];
+        if (m + 1 > path_cap) { free(ok); free(depth); return 3; }
+        int32_t *prow = path + (int64_t)b * path_cap;
+        int32_t *crow = committed_tok + (int64_t)b * path_cap;
+        for (int j = 0; j < path_cap; ++j) { prow[j] = -1; crow[j] = -1; }
+        int t = best;
+        for (int j = m; j >= 0; --j) { prow[j] = t; t = par[t]; }
+        for (int j = 1; j <= m; ++j) crow[j - 1] = tok[prow[j]];
+        crow[m] = am[best];
+        accept_len[b] = m;
+        bonus_tok[b] = am[best];
+        free(ok); free(depth);
+    }
+    return 0;
+}
+
+/*
+ * KV compaction of the accepted path, for all layers, KV heads and both K and V:
+ *     cache[P_b + j] <- cache_old[P_b + a_j]   j = 0..m     (read all, then write)
+ *     new_prefix_len[b] = P_b + m + 1
+ * The paper does not describe this step; it is what any tree verifier must do
+ * so that the cache holds only committed tokens.  Rows are copied as raw bytes.
+ * Layer l's cache starts layer_stride elements after layer l-1's.
+ * moved_idx (may be NULL) [B,path_cap,2] receives (src_slot, dst_slot), -1 padded.
+ * new_prefix_len may alias prefix_len.
+ */
+int oracle_kv_compact(int L, int B, int Hkv, int D, int elem_bytes,
+                      void *k, void *v, int64_t layer_stride,
+                      int64_t kv_sb, int64_t kv_sh, int64_t kv_st,
+                      const int32_t *block_table, int block_size, int max_blocks,
+                      const int32_t *prefix_len, const int32_t *path, int path_cap,
+                      const int32_t *accept_len, int32_t *new_prefix_len, int32_t *moved_idx)
+{
+    size_t row_bytes = (size_t)D * elem_bytes;
+    for (int b = 0; b < B; ++b) {
+        int P = prefix_len[b];
+        int m = accept_len[b];
+        const int32_t *prow = path + (int64_t)b * path_cap;
+        if (m < 0 || m + 1 > path_cap) return 3;
+        if (moved_idx)
+            for (int j = 0; j < path_cap; ++j) {
+                moved_idx[((int64_t)b * path_cap + j) * 2 + 0] = j <= m ? P + prow[j] : -1;
+                moved_idx[((int64_t)b * path_cap + j) * 2 + 1] = j <= m ? P + j : -1;
+            }
+        unsigned char *tmp = malloc(row_bytes * (size_t)(m + 1));
+        if (!tmp) return 2;
+        for (int l = 0; l < L; ++l)
+            for (int which = 0; which < 2; ++which) {
+                unsigned char *base = (unsigned char *)(which ? v : k) +
+                                      (size_t)l * layer_stride * elem_bytes;
+                for (int hk = 0; hk < Hkv; ++hk) {
+                    for (int j = 0; j <= m; ++j) {
+                        int64_t off = kv_row_offset(b, hk, P + prow[j], kv_sb, kv_sh, kv_st,
+                                                    block_table, block_size, max_blocks);
+                        memcpy(tmp + row_bytes * j, base + off * elem_bytes, row_bytes);
+                    }
+                    for (int j = 0; j <= m; ++j) {
+                        int64_t off = kv_row_offset(b, hk, P + j, kv_sb, kv_sh, kv_st,
+                                                    block_table, block_size, max_blocks);
+                        memcpy(base + off * elem_bytes, tmp + row_bytes * j, row_bytes);
+                    }
+                }
+            }
+        free(tmp);
+    }
+    for (int b = 0; b < B; ++b)
+        new_prefix_len[b] = prefix_len[b] + accept_len[b] + 1;
+    return 0;
+}
