@@ -1,0 +1,187 @@
+/*
+ * specvlm.h -- C ABI of libspecvlm: the target model's verification step over a
+ * draft token tree (SpecVLM Sec. 3.1: in every speculative round the target
+ * verifies the drafted tokens in ONE forward pass and the incorrect ones are
+ * discarded; Sec. 4.1: the draft is an EAGLE-2 style token tree with Top-K 10,
+ * 60 tokens, depth 7; evaluation at temperature 0, batch 1).
+ *
+ * Conventions
+ *  - Every pointer named *_dev is DEVICE memory owned by the caller; the library
+ *    allocates nothing, keeps no pointer after return and is re-entrant.
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *    default stream).  Calls are asynchronous; outputs are valid once the stream
+ *    has reached them.
+ *  - Every function returns a specvlm_status.  Scalar arguments are validated on
+ *    the host without synchronising.  Data-dependent violations (malformed parent
+ *    array, node counts or tokens out of range) are reported by OR-ing
+ *    SPECVLM_ERR_* bits into the optional device word `err_flag_dev`; the kernels
+ *    then leave that request's outputs defined but unspecified and never touch
+ *    memory outside the given buffers.
+ *  - Tree convention: node 0 is the root (the token the target committed last,
+ *    Fig. 3a), parent[0] = -1, 0 <= parent[i] < i for i >= 1.  At most 64 nodes.
+ *  - Strides are in ELEMENTS of the tensor's type.  The innermost (head_dim or
+ *    vocab) dimension is always contiguous.
+ */
+#ifndef SPECVLM_H
+#define SPECVLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum specvlm_status {
+    SPECVLM_OK = 0,
+    SPECVLM_INVALID_ARG = 1,         /* null pointer, bad dimension, misaligned pointer/stride */
+    SPECVLM_UNSUPPORTED = 2,         /* legal but not implemented dtype/layout combination   */
+    SPECVLM_WORKSPACE_TOO_SMALL = 3,
+    SPECVLM_HIP_ERROR = 4            /* launch failed; see specvlm_last_hip_error()           */
+} specvlm_status;
+
+typedef enum specvlm_dtype {
+    SPECVLM_BF16 = 0,                /* bfloat16 in, fp32 accumulate/softmax, bfloat16 out */
+    SPECVLM_F32 = 1                  /* IEEE fp32 throughout                                */
+} specvlm_dtype;
+
+/* bits of *err_flag_dev */
+#define SPECVLM_ERR_BAD_PARENT   1   /* parent[0] != -1 or parent[i] not in [0,i)            */
+#define SPECVLM_ERR_BAD_NUM_NODES 2  /* num_nodes[b] not in [1, N_max]                       */
+#define SPECVLM_ERR_BAD_LENGTH   4   /* prefix_len[b] < 0 or prefix_len+num_nodes > capacity */
+#define SPECVLM_ERR_PATH_TOO_LONG 8  /* an accepted path would not fit in path_cap           */
+#define SPECVLM_ERR_BAD_BLOCK    16  /* block_table entry outside [0, num_blocks)            */
+
+#define SPECVLM_MAX_NODES 64
+#define SPECVLM_PAGE_SIZE 16
+
+/*
+ * Geometry of one attention layer's tensors.
+ *
+ *   q, o     : [B, N_max, H_q, D]      via (q|o)_stride_b / _n / _h
+ *   K, V     : contiguous (paged == 0): [B, H_kv, kv_capacity, D] via kv_stride_b (request),
+ *              kv_stride_h, kv_stride_t (token);
+ *              paged (paged == 1): [num_blocks, H_kv, 16, D] via kv_stride_b (BLOCK),
+ *              kv_stride_h, kv_stride_t, addressed through block_table[B, max_blocks_per_req]
+ *              (logical slot s of request b lives in block block_table[b][s/16], row s%16).
+ *   K and V share one geometry.  H_q must be a multiple of H_kv (query head h reads KV
+ *   head h / (H_q/H_kv)).  D is 64 or 128.  N_max <= 64.
+ */
+typedef struct specvlm_attn_desc {
+    int32_t dtype;                 /* specvlm_dtype */
+    int32_t B, H_q, H_kv, D, N_max;
+    float   softmax_scale;         /* 0 selects 1/sqrt(D) */
+    int32_t paged;
+    int32_t block_size;            /* must be 16 when paged */
+    int32_t max_blocks_per_req;    /* second dimension of block_table (paged only) */
+    int32_t num_blocks;            /* physical blocks in the pool (paged only)     */
+    int32_t kv_capacity;           /* slots per request (contiguous); paged: max_blocks_per_req*16 */
+    int32_t num_splits;            /* key-range splits per (request, head); 0 lets the library choose */
+    int64_t q_stride_b, q_stride_n, q_stride_h;
+    int64_t o_stride_b, o_stride_n, o_stride_h;
+    int64_t kv_stride_b, kv_stride_h, kv_stride_t;
+} specvlm_attn_desc;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t specvlm_version(void);
+
+/* hipError_t of the most recent failed HIP call made by this thread's library calls (0 if none). */
+int32_t specvlm_last_hip_error(void);
+
+/*
+ * Scratch bytes specvlm_tree_verify_attn needs for `desc` (split-key partial
+ * results).  Returns 0 when desc is invalid.  The workspace is device memory,
+ * 256-byte aligned, used only during the call's kernels; its contents need no
+ * initialisation and are garbage afterwards.
+ */
+size_t specvlm_tree_verify_attn_workspace_bytes(const specvlm_attn_desc *desc);
+
+/*
+ * Tree-masked verification attention for ONE layer (Sec. 3.1 "verifies ... in a
+ * single forward pass", Sec. 4.1 "tree attention"; Sec. 3.2: the whole KV cache
+ * is streamed from HBM once per step).  For request b, query head h and tree
+ * node i < num_nodes[b]:
+ *     J(i) = {0 .. prefix_len[b]-1}  U  {prefix_len[b] + j : j is i or an ancestor of i}
+ *     o[b,i,h,:] = softmax_{j in J(i)}(scale * q[b,i,h,:] . K[b,kv(h),j,:]) . V[b,kv(h),j,:]
+ *     lse[b,h,i] = natural-log-sum-exp of the scaled scores over J(i)   (optional)
+ * Precondition: the caller has already written the tree tokens' K/V rows into
+ * logical slots [prefix_len[b], prefix_len[b]+num_nodes[b]) of the cache, with
+ * position encoding applied.  Rows i >= num_nodes[b] of o / lse are not written.
+ * Slots at or beyond prefix_len[b]+num_nodes[b] are never read.
+ *
+ *   q_dev, o_dev         device, desc->dtype, geometry from desc; 16-byte aligned rows
+ *   k_cache_dev, v_cache_dev  device, desc->dtype, read-only here
+ *   block_table_dev      device int32 [B, max_blocks_per_req]; NULL iff !paged
+ *   prefix_len_dev       device int32 [B]
+ *   num_nodes_dev        device int32 [B], or NULL meaning N_max for every request
+ *   parent_dev           device int32 [B, N_max]
+ *   lse_dev              device fp32 [B, H_q, N_max] or NULL
+ *   workspace_dev/bytes  see specvlm_tree_verify_attn_workspace_bytes
+ *   err_flag_dev         device int32 or NULL
+ */
+int32_t specvlm_tree_verify_attn(const specvlm_attn_desc *desc,
+                                 const void *q_dev, const void *k_cache_dev, const void *v_cache_dev,
+                                 const int32_t *block_table_dev, const int32_t *prefix_len_dev,
+                                 const int32_t *num_nodes_dev, const int32_t *parent_dev,
+                                 void *o_dev, float *lse_dev,
+                                 void *workspace_dev, size_t workspace_bytes,
+                                 int32_t *err_flag_dev, void *stream);
+
+/*
+ * Greedy target token per tree node (temperature 0, Sec. 4.1):
+ *     amax[b,i] = the LOWEST v with logits[b,i,v] == max_v' logits[b,i,v']
+ * (values compare as real numbers, -0 == +0; precondition: no NaN; an all -inf
+ * row gives 0).  Rows i >= num_nodes[b] get -1.
+ *   logits_dev  device, dtype, element (b,i,v) at b*stride_b + i*stride_n + v
+ *   amax_dev    device int32 [B, N_max]
+ */
+int32_t specvlm_node_argmax(int32_t dtype, int32_t B, int32_t N_max, int32_t V,
+                            const void *logits_dev, int64_t stride_b, int64_t stride_n,
+                            const int32_t *num_nodes_dev, int32_t *amax_dev, void *stream);
+
+/*
+ * Greedy acceptance walk (Sec. 3.1: incorrect drafted tokens are discarded;
+ * decoding stays lossless).  For i >= 1, node i matches when
+ * draft_tok[b,i] == amax[b,parent[b,i]]; a node is accepted when it and all its
+ * ancestors below the root match.  best = the accepted node of greatest depth
+ * (lowest node index on ties); path = root..best = a_0..a_m.
+ *   accept_len_dev    int32 [B]            m, the number of accepted DRAFT nodes
+ *   path_dev          int32 [B, path_cap]  a_0..a_m, then -1
+ *   bonus_tok_dev     int32 [B]            amax[b, best]: the next round's root token
+ *   committed_tok_dev int32 [B, path_cap]  draft_tok[a_1..a_m], bonus_tok, then -1
+ *                                          (the m+1 tokens this round emits: sigma counts these)
+ * draft_tok[b,0] is ignored.  1 <= path_cap <= 64; a path that does not fit sets
+ * SPECVLM_ERR_PATH_TOO_LONG and nodes deeper than path_cap-1 are not accepted.
+ */
+int32_t specvlm_tree_accept(int32_t B, int32_t N_max, int32_t path_cap,
+                            const int32_t *parent_dev, const int32_t *draft_tok_dev,
+                            const int32_t *amax_dev, const int32_t *num_nodes_dev,
+                            int32_t *accept_len_dev, int32_t *path_dev, int32_t *bonus_tok_dev,
+                            int32_t *committed_tok_dev, int32_t *err_flag_dev, void *stream);
+
+/*
+ * Compaction of the accepted path's K/V rows, all layers in one call (not spelled
+ * out by the paper; it is what keeps the cache holding committed tokens only, so
+ * that the next round's prefix is contiguous).  For every layer, KV head, and for
+ * K and V:
+ *     cache[prefix_len[b] + j] <- OLD cache[prefix_len[b] + path[b,j]],  j = 0..accept_len[b]
+ * (gather semantics: all sources are read before any destination is written), then
+ *     new_prefix_len[b] = prefix_len[b] + accept_len[b] + 1.
+ * Layer l's cache is k_base_dev + l*layer_stride elements (same for V), or, when
+ * k_layer_ptrs_dev / v_layer_ptrs_dev are non-NULL, the l-th pointer of those DEVICE
+ * arrays of L device pointers (then k_base_dev/v_base_dev/layer_stride are ignored).
+ * Only desc's dtype, B, H_kv, D, paged, block_size, max_blocks_per_req, kv_capacity
+ * and kv_stride_* are used.  new_prefix_len_dev may alias prefix_len_dev.
+ *   moved_idx_dev  optional int32 [B, path_cap, 2]: (src_slot, dst_slot) per j, -1 padded.
+ */
+int32_t specvlm_kv_compact(const specvlm_attn_desc *desc, int32_t L,
+                           void *k_base_dev, void *v_base_dev, int64_t layer_stride,
+                           void *const *k_layer_ptrs_dev, void *const *v_layer_ptrs_dev,
+                           const int32_t *block_table_dev, const int32_t *prefix_len_dev,
+                           const int32_t *path_dev, int32_t path_cap, const int32_t *accept_len_dev,
+                           int32_t *new_prefix_len_dev, int32_t *moved_idx_dev, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECVLM_H */

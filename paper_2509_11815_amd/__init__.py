@@ -1,0 +1,18 @@
+"""MI355X-native tree-verification step of SpecVLM-style speculative decoding.
+
+The product is ``libspecvlm.so`` (hand-written HIP for gfx950 behind the C ABI of
+``include/specvlm.h``); this package is its argument-marshalling Python binding.
+PyTorch is used for device memory and streams only.
+"""
+from .binding import (  # noqa: F401
+    AttnDesc,
+    SpecvlmError,
+    lib,
+    load_library,
+    specvlm_kv_compact,
+    specvlm_node_argmax,
+    specvlm_tree_accept,
+    specvlm_tree_verify_attn,
+    specvlm_tree_verify_attn_workspace_bytes,
+    specvlm_version,
+)

@@ -1,0 +1,233 @@
+"""ctypes binding of libspecvlm.so: same names as the C entry points, marshalling only.
+
+Every step runs in the library's HIP kernels; there is no fallback.  Importing this module
+does not need the library; the first call loads it and raises if it has not been built
+(``python -m paper_2509_11815_amd.build``).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+SPECVLM_BF16, SPECVLM_F32 = 0, 1
+STATUS = {0: "OK", 1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE_TOO_SMALL", 4: "HIP_ERROR"}
+ERR_BITS = {1: "BAD_PARENT", 2: "BAD_NUM_NODES", 4: "BAD_LENGTH", 8: "PATH_TOO_LONG", 16: "BAD_BLOCK"}
+
+EXPORTS = ["specvlm_version", "specvlm_last_hip_error", "specvlm_tree_verify_attn_workspace_bytes",
+           "specvlm_tree_verify_attn", "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_kv_compact"]
+
+
+class SpecvlmError(RuntimeError):
+    pass
+
+
+class AttnDesc(ctypes.Structure):
+    """Mirror of specvlm_attn_desc."""
+    _fields_ = [("dtype", ctypes.c_int32), ("B", ctypes.c_int32), ("H_q", ctypes.c_int32),
+                ("H_kv", ctypes.c_int32), ("D", ctypes.c_int32), ("N_max", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float), ("paged", ctypes.c_int32),
+                ("block_size", ctypes.c_int32), ("max_blocks_per_req", ctypes.c_int32),
+                ("num_blocks", ctypes.c_int32), ("kv_capacity", ctypes.c_int32),
+                ("num_splits", ctypes.c_int32),
+                ("q_stride_b", ctypes.c_int64), ("q_stride_n", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+                ("o_stride_b", ctypes.c_int64), ("o_stride_n", ctypes.c_int64), ("o_stride_h", ctypes.c_int64),
+                ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64), ("kv_stride_t", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def load_library(path: str | None = None) -> ctypes.CDLL:
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or _build.LIB
+    if not os.path.exists(path):
+        raise SpecvlmError(f"{path} is missing: build it with `python -m paper_2509_11815_amd.build` "
+                           "(there is no fallback path)")
+    L = ctypes.CDLL(path)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.specvlm_version.restype = i32
+    L.specvlm_last_hip_error.restype = i32
+    L.specvlm_tree_verify_attn_workspace_bytes.restype = ctypes.c_size_t
+    L.specvlm_tree_verify_attn_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc)]
+    L.specvlm_tree_verify_attn.restype = i32
+    L.specvlm_tree_verify_attn.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 9 + [vp, ctypes.c_size_t, vp, vp]
+    L.specvlm_node_argmax.restype = i32
+    L.specvlm_node_argmax.argtypes = [i32, i32, i32, i32, vp, i64, i64, vp, vp, vp]
+    L.specvlm_tree_accept.restype = i32
+    L.specvlm_tree_accept.argtypes = [i32, i32, i32] + [vp] * 10
+    L.specvlm_kv_compact.restype = i32
+    L.specvlm_kv_compact.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, vp, i64, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    _lib = L
+    return L
+
+
+def lib() -> ctypes.CDLL:
+    return load_library()
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        extra = f" (hipError {lib().specvlm_last_hip_error()})" if rc == 4 else ""
+        raise SpecvlmError(f"{what}: {STATUS.get(rc, rc)}{extra}")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return SPECVLM_BF16
+    if t.dtype == torch.float32:
+        return SPECVLM_F32
+    raise TypeError(f"bfloat16 or float32 expected, got {t.dtype}")
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev_i32(t, name):
+    if t is None:
+        return None
+    if not (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous int32 device tensor")
+    return t
+
+
+def make_attn_desc(q, k_cache, out=None, *, block_table=None, softmax_scale=0.0, num_splits=0) -> AttnDesc:
+    """Fill a specvlm_attn_desc from tensor shapes and strides.
+
+    q [B,N_max,H_q,D]; contiguous cache [B,H_kv,capacity,D]; paged cache [num_blocks,H_kv,16,D]."""
+    B, N_max, H_q, D = q.shape
+    d = AttnDesc()
+    d.dtype = _dtype_code(q)
+    d.B, d.H_q, d.H_kv, d.D, d.N_max = B, H_q, k_cache.shape[1], D, N_max
+    d.softmax_scale = float(softmax_scale)
+    d.num_splits = int(num_splits)
+    if q.stride(3) != 1 or k_cache.stride(3) != 1:
+        raise ValueError("innermost dimension must be contiguous")
+    d.q_stride_b, d.q_stride_n, d.q_stride_h = q.stride(0), q.stride(1), q.stride(2)
+    o = q if out is None else out
+    d.o_stride_b, d.o_stride_n, d.o_stride_h = o.stride(0), o.stride(1), o.stride(2)
+    d.kv_stride_b, d.kv_stride_h, d.kv_stride_t = k_cache.stride(0), k_cache.stride(1), k_cache.stride(2)
+    if block_table is not None:
+        d.paged, d.block_size = 1, k_cache.shape[2]
+        d.max_blocks_per_req = block_table.shape[1]
+        d.num_blocks = k_cache.shape[0]
+        d.kv_capacity = d.max_blocks_per_req * d.block_size
+    else:
+        d.paged, d.block_size, d.max_blocks_per_req, d.num_blocks = 0, 0, 0, 0
+        d.kv_capacity = k_cache.shape[2]
+    return d
+
+
+def specvlm_version() -> int:
+    return int(lib().specvlm_version())
+
+
+def specvlm_tree_verify_attn_workspace_bytes(desc: AttnDesc) -> int:
+    return int(lib().specvlm_tree_verify_attn_workspace_bytes(ctypes.byref(desc)))
+
+
+def specvlm_tree_verify_attn(q, k_cache, v_cache, prefix_len, parent, *, num_nodes=None, block_table=None,
+                             out=None, lse=None, workspace=None, err_flag=None, softmax_scale=0.0,
+                             num_splits=0, desc=None, stream=None):
+    """One layer of tree-masked verification attention.  Returns `out` ([B,N_max,H_q,D])."""
+    if out is None:
+        out = torch.zeros_like(q)
+    if desc is None:
+        desc = make_attn_desc(q, k_cache, out, block_table=block_table, softmax_scale=softmax_scale,
+                              num_splits=num_splits)
+    if k_cache.stride() != v_cache.stride() or k_cache.shape != v_cache.shape:
+        raise ValueError("K and V caches must share one geometry")
+    need = specvlm_tree_verify_attn_workspace_bytes(desc)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().specvlm_tree_verify_attn(
+        ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(_dev_i32(block_table, "block_table")),
+        _ptr(_dev_i32(prefix_len, "prefix_len")), _ptr(_dev_i32(num_nodes, "num_nodes")),
+        _ptr(_dev_i32(parent, "parent")), _ptr(out), _ptr(lse), _ptr(workspace), ctypes.c_size_t(wbytes),
+        _ptr(err_flag), _stream(stream))
+    _check(rc, "specvlm_tree_verify_attn")
+    return out
+
+
+def specvlm_node_argmax(logits, *, num_nodes=None, out=None, stream=None):
+    """logits [B,N_max,V] -> int32 [B,N_max] lowest index of each row's maximum."""
+    B, N_max, V = logits.shape
+    if logits.stride(2) != 1:
+        raise ValueError("vocab dimension must be contiguous")
+    if out is None:
+        out = torch.empty((B, N_max), dtype=torch.int32, device=logits.device)
+    rc = lib().specvlm_node_argmax(_dtype_code(logits), B, N_max, V, _ptr(logits), logits.stride(0),
+                                   logits.stride(1), _ptr(_dev_i32(num_nodes, "num_nodes")), _ptr(out),
+                                   _stream(stream))
+    _check(rc, "specvlm_node_argmax")
+    return out
+
+
+def specvlm_tree_accept(parent, draft_tok, amax, *, num_nodes=None, path_cap=8, err_flag=None, stream=None):
+    """Returns (accept_len [B], path [B,path_cap], bonus_tok [B], committed_tok [B,path_cap])."""
+    B, N_max = parent.shape
+    dev = parent.device
+    accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+    path = torch.empty((B, path_cap), dtype=torch.int32, device=dev)
+    bonus = torch.empty(B, dtype=torch.int32, device=dev)
+    committed = torch.empty((B, path_cap), dtype=torch.int32, device=dev)
+    rc = lib().specvlm_tree_accept(B, N_max, path_cap, _ptr(_dev_i32(parent, "parent")),
+                                   _ptr(_dev_i32(draft_tok, "draft_tok")), _ptr(_dev_i32(amax, "amax")),
+                                   _ptr(_dev_i32(num_nodes, "num_nodes")), _ptr(accept_len), _ptr(path),
+                                   _ptr(bonus), _ptr(committed), _ptr(err_flag), _stream(stream))
+    _check(rc, "specvlm_tree_accept")
+    return accept_len, path, bonus, committed
+
+
+def specvlm_kv_compact(k_caches, v_caches, prefix_len, path, accept_len, *, block_table=None,
+                       new_prefix_len=None, moved_idx=None, layer_ptrs=None, stream=None):
+    """In-place compaction.  k_caches/v_caches: one tensor [L, <per-layer cache dims>] (layer stride taken
+    from the tensor), or with `layer_ptrs=(k_ptrs, v_ptrs)` (int64 device tensors of L addresses) a single
+    layer's tensor that only provides the geometry.  Returns (new_prefix_len, moved_idx)."""
+    B, path_cap = path.shape
+    dev = path.device
+    if new_prefix_len is None:
+        new_prefix_len = torch.empty(B, dtype=torch.int32, device=dev)
+    if layer_ptrs is None:
+        L = k_caches.shape[0]
+        layer0 = k_caches[0]
+        layer_stride = k_caches.stride(0)
+        kb, vb, kp, vp = _ptr(k_caches), _ptr(v_caches), None, None
+        if k_caches.stride() != v_caches.stride():
+            raise ValueError("K and V caches must share one geometry")
+    else:
+        kp_t, vp_t = layer_ptrs
+        L = kp_t.numel()
+        layer0 = k_caches
+        layer_stride = 0
+        kb, vb, kp, vp = None, None, _ptr(kp_t), _ptr(vp_t)
+    d = AttnDesc()
+    d.dtype = _dtype_code(layer0)
+    d.B, d.H_q, d.H_kv, d.D, d.N_max = B, layer0.shape[1], layer0.shape[1], layer0.shape[3], 64
+    d.kv_stride_b, d.kv_stride_h, d.kv_stride_t = layer0.stride(0), layer0.stride(1), layer0.stride(2)
+    if block_table is not None:
+        d.paged, d.block_size = 1, layer0.shape[2]
+        d.max_blocks_per_req = block_table.shape[1]
+        d.num_blocks = layer0.shape[0]
+        d.kv_capacity = d.max_blocks_per_req * d.block_size
+    else:
+        d.kv_capacity = layer0.shape[2]
+    rc = lib().specvlm_kv_compact(ctypes.byref(d), L, kb, vb, layer_stride, kp, vp,
+                                  _ptr(_dev_i32(block_table, "block_table")),
+                                  _ptr(_dev_i32(prefix_len, "prefix_len")), _ptr(_dev_i32(path, "path")),
+                                  path_cap, _ptr(_dev_i32(accept_len, "accept_len")), _ptr(new_prefix_len),
+                                  _ptr(moved_idx), _stream(stream))
+    _check(rc, "specvlm_kv_compact")
+    return new_prefix_len, moved_idx

@@ -1,0 +1,149 @@
+// C ABI of libspecvlm: host-side argument checks and kernel dispatch.  See include/specvlm.h
+// for the contract of every entry point.
+#include <math.h>
+
+#include "common.hpp"
+
+namespace specvlm {
+
+static thread_local int32_t g_last_hip_error = 0;
+void note_hip_error(hipError_t e) { g_last_hip_error = static_cast<int32_t>(e); }
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Geometry checks common to attention and compaction.
+static int32_t check_kv_geometry(const specvlm_attn_desc& d) {
+    if (d.dtype != SPECVLM_BF16 && d.dtype != SPECVLM_F32) return SPECVLM_INVALID_ARG;
+    if (d.B < 1 || d.H_kv < 1 || (d.D != 64 && d.D != 128)) return SPECVLM_INVALID_ARG;
+    const int vec = d.dtype == SPECVLM_BF16 ? 8 : 4;                 // elements per 16 bytes
+    if (d.kv_stride_t < d.D || d.kv_stride_t % vec || d.kv_stride_h % vec || d.kv_stride_b % vec)
+        return SPECVLM_INVALID_ARG;
+    if (d.kv_stride_h < 0 || d.kv_stride_b < 0) return SPECVLM_INVALID_ARG;
+    if (d.paged) {
+        if (d.block_size != SPECVLM_PAGE_SIZE || d.max_blocks_per_req < 1 || d.num_blocks < 1)
+            return SPECVLM_INVALID_ARG;
+    } else if (d.kv_capacity < 1) {
+        return SPECVLM_INVALID_ARG;
+    }
+    return SPECVLM_OK;
+}
+
+static int32_t check_attn_desc(const specvlm_attn_desc& d) {
+    int32_t rc = check_kv_geometry(d);
+    if (rc) return rc;
+    if (d.H_q < 1 || d.H_q % d.H_kv) return SPECVLM_INVALID_ARG;
+    if (d.N_max < 1 || d.N_max > SPECVLM_MAX_NODES) return SPECVLM_INVALID_ARG;
+    if (!(d.softmax_scale >= 0.f) || isinf(d.softmax_scale)) return SPECVLM_INVALID_ARG;
+    if (d.num_splits < 0) return SPECVLM_INVALID_ARG;
+    const int vec = d.dtype == SPECVLM_BF16 ? 8 : 4;
+    const int64_t st[6] = {d.q_stride_b, d.q_stride_n, d.q_stride_h, d.o_stride_b, d.o_stride_n, d.o_stride_h};
+    for (int64_t s : st)
+        if (s < 0 || s % vec) return SPECVLM_INVALID_ARG;
+    if (d.q_stride_h < d.D || d.o_stride_h < d.D) return SPECVLM_INVALID_ARG;
+    return SPECVLM_OK;
+}
+
+}  // namespace specvlm
+
+using namespace specvlm;
+
+extern "C" {
+
+int32_t specvlm_version(void) { return 100; }
+
+int32_t specvlm_last_hip_error(void) { return g_last_hip_error; }
+
+size_t specvlm_tree_verify_attn_workspace_bytes(const specvlm_attn_desc* desc) {
+    if (!desc || check_attn_desc(*desc)) return 0;
+    if (desc->dtype == SPECVLM_F32) return 256;
+    return attn_mfma_workspace_bytes(*desc);
+}
+
+int32_t specvlm_tree_verify_attn(const specvlm_attn_desc* desc, const void* q_dev, const void* k_cache_dev,
+                                 const void* v_cache_dev, const int32_t* block_table_dev,
+                                 const int32_t* prefix_len_dev, const int32_t* num_nodes_dev,
+                                 const int32_t* parent_dev, void* o_dev, float* lse_dev,
+                                 void* workspace_dev, size_t workspace_bytes, int32_t* err_flag_dev,
+                                 void* stream) {
+    if (!desc) return SPECVLM_INVALID_ARG;
+    int32_t rc = check_attn_desc(*desc);
+    if (rc) return rc;
+    if (!q_dev || !k_cache_dev || !v_cache_dev || !prefix_len_dev || !parent_dev || !o_dev)
+        return SPECVLM_INVALID_ARG;
+    if ((desc->paged != 0) != (block_table_dev != nullptr)) return SPECVLM_INVALID_ARG;
+    if (!aligned16(q_dev) || !aligned16(k_cache_dev) || !aligned16(v_cache_dev) || !aligned16(o_dev))
+        return SPECVLM_INVALID_ARG;
+    AttnArgs a;
+    a.d = *desc;
+    a.scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf(static_cast<float>(desc->D));
+    a.q = q_dev; a.k = k_cache_dev; a.v = v_cache_dev;
+    a.block_table = block_table_dev; a.prefix_len = prefix_len_dev; a.num_nodes = num_nodes_dev;
+    a.parent = parent_dev; a.o = o_dev; a.lse = lse_dev;
+    a.workspace = workspace_dev; a.workspace_bytes = workspace_bytes;
+    a.err_flag = err_flag_dev; a.stream = static_cast<hipStream_t>(stream);
+    if (desc->dtype == SPECVLM_F32) return launch_attn_valu(a);
+    // num_splits < 0 is rejected above; the special value 1000 selects the bf16 VALU kernel,
+    // kept only to measure what the vector ALUs reach on this step.
+    if (desc->num_splits == 1000) return launch_attn_valu(a);
+    const size_t need = attn_mfma_workspace_bytes(*desc);
+    if (attn_mfma_pick_splits(*desc) > 1) {
+        if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255u)) return SPECVLM_INVALID_ARG;
+        if (workspace_bytes < need) return SPECVLM_WORKSPACE_TOO_SMALL;
+    }
+    return launch_attn_mfma(a);
+}
+
+int32_t specvlm_node_argmax(int32_t dtype, int32_t B, int32_t N_max, int32_t V, const void* logits_dev,
+                            int64_t stride_b, int64_t stride_n, const int32_t* num_nodes_dev,
+                            int32_t* amax_dev, void* stream) {
+    if (dtype != SPECVLM_BF16 && dtype != SPECVLM_F32) return SPECVLM_INVALID_ARG;
+    if (B < 1 || N_max < 1 || N_max > SPECVLM_MAX_NODES || V < 1) return SPECVLM_INVALID_ARG;
+    if (!logits_dev || !amax_dev || stride_b < 0 || stride_n < V) return SPECVLM_INVALID_ARG;
+    const uintptr_t es = dtype == SPECVLM_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(logits_dev) % es) return SPECVLM_INVALID_ARG;
+    return launch_node_argmax(dtype, B, N_max, V, logits_dev, stride_b, stride_n, num_nodes_dev, amax_dev,
+                              static_cast<hipStream_t>(stream));
+}
+
+int32_t specvlm_tree_accept(int32_t B, int32_t N_max, int32_t path_cap, const int32_t* parent_dev,
+                            const int32_t* draft_tok_dev, const int32_t* amax_dev,
+                            const int32_t* num_nodes_dev, int32_t* accept_len_dev, int32_t* path_dev,
+                            int32_t* bonus_tok_dev, int32_t* committed_tok_dev, int32_t* err_flag_dev,
+                            void* stream) {
+    if (B < 1 || N_max < 1 || N_max > SPECVLM_MAX_NODES || path_cap < 1 || path_cap > SPECVLM_MAX_NODES)
+        return SPECVLM_INVALID_ARG;
+    if (!parent_dev || !draft_tok_dev || !amax_dev || !accept_len_dev || !path_dev || !bonus_tok_dev ||
+        !committed_tok_dev)
+        return SPECVLM_INVALID_ARG;
+    return launch_tree_accept(B, N_max, path_cap, parent_dev, draft_tok_dev, amax_dev, num_nodes_dev,
+                              accept_len_dev, path_dev, bonus_tok_dev, committed_tok_dev, err_flag_dev,
+                              static_cast<hipStream_t>(stream));
+}
+
+int32_t specvlm_kv_compact(const specvlm_attn_desc* desc, int32_t L, void* k_base_dev, void* v_base_dev,
+                           int64_t layer_stride, void* const* k_layer_ptrs_dev, void* const* v_layer_ptrs_dev,
+                           const int32_t* block_table_dev, const int32_t* prefix_len_dev,
+                           const int32_t* path_dev, int32_t path_cap, const int32_t* accept_len_dev,
+                           int32_t* new_prefix_len_dev, int32_t* moved_idx_dev, void* stream) {
+    if (!desc) return SPECVLM_INVALID_ARG;
+    int32_t rc = check_kv_geometry(*desc);
+    if (rc) return rc;
+    if (L < 1 || L > 32767 || desc->H_kv > 65535 || desc->B > 65535) return SPECVLM_INVALID_ARG;
+    if (path_cap < 1 || path_cap > SPECVLM_MAX_NODES) return SPECVLM_INVALID_ARG;
+    if (!prefix_len_dev || !path_dev || !accept_len_dev || !new_prefix_len_dev) return SPECVLM_INVALID_ARG;
+    if ((desc->paged != 0) != (block_table_dev != nullptr)) return SPECVLM_INVALID_ARG;
+    const bool by_ptr = k_layer_ptrs_dev != nullptr || v_layer_ptrs_dev != nullptr;
+    if (by_ptr) {
+        if (!k_layer_ptrs_dev || !v_layer_ptrs_dev) return SPECVLM_INVALID_ARG;
+    } else {
+        if (!k_base_dev || !v_base_dev || !aligned16(k_base_dev) || !aligned16(v_base_dev)) return SPECVLM_INVALID_ARG;
+        const int vec = desc->dtype == SPECVLM_BF16 ? 8 : 4;
+        if (layer_stride < 0 || layer_stride % vec) return SPECVLM_INVALID_ARG;
+    }
+    return launch_kv_compact(*desc, L, k_base_dev, v_base_dev, layer_stride, k_layer_ptrs_dev,
+                             v_layer_ptrs_dev, block_table_dev, prefix_len_dev, path_dev, path_cap,
+                             accept_len_dev, new_prefix_len_dev, moved_idx_dev,
+                             static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

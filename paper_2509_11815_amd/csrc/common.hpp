@@ -1,0 +1,88 @@
+// Internal declarations shared by the HIP translation units of libspecvlm (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "specvlm.h"
+
+namespace specvlm {
+
+// Records a failed HIP call for specvlm_last_hip_error().
+void note_hip_error(hipError_t e);
+
+inline int32_t check_launch() {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        note_hip_error(e);
+        return SPECVLM_HIP_ERROR;
+    }
+    return SPECVLM_OK;
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// Kernel-side view of the K/V cache geometry of one request's rows.
+struct KvGeom {
+    int64_t stride_b, stride_h, stride_t;   // elements
+    const int32_t* block_table;             // nullptr => contiguous
+    int32_t max_blocks;                     // per request (paged)
+    int32_t num_blocks;                     // pool size (paged)
+    int32_t capacity;                       // slots per request
+};
+
+// Element offset of logical slot `slot` of request b, KV head hk.  `slot` must be < capacity.
+__device__ __forceinline__ int64_t kv_row_offset(const KvGeom& g, int b, int hk, int slot) {
+    if (g.block_table) {
+        int blk = g.block_table[static_cast<int64_t>(b) * g.max_blocks + (slot >> 4)];
+        blk = min(max(blk, 0), g.num_blocks - 1);
+        return blk * g.stride_b + hk * g.stride_h + (slot & 15) * g.stride_t;
+    }
+    return b * g.stride_b + hk * g.stride_h + slot * g.stride_t;
+}
+
+// Launchers (defined next to their kernels).  All return a specvlm_status.
+int32_t launch_node_argmax(int32_t dtype, int32_t B, int32_t N_max, int32_t V, const void* logits,
+                           int64_t stride_b, int64_t stride_n, const int32_t* num_nodes,
+                           int32_t* amax, hipStream_t stream);
+
+int32_t launch_tree_accept(int32_t B, int32_t N_max, int32_t path_cap, const int32_t* parent,
+                           const int32_t* draft_tok, const int32_t* amax, const int32_t* num_nodes,
+                           int32_t* accept_len, int32_t* path, int32_t* bonus_tok,
+                           int32_t* committed_tok, int32_t* err_flag, hipStream_t stream);
+
+int32_t launch_kv_compact(const specvlm_attn_desc& d, int32_t L, void* k_base, void* v_base,
+                          int64_t layer_stride, void* const* k_ptrs, void* const* v_ptrs,
+                          const int32_t* block_table, const int32_t* prefix_len, const int32_t* path,
+                          int32_t path_cap, const int32_t* accept_len, int32_t* new_prefix_len,
+                          int32_t* moved_idx, hipStream_t stream);
+
+struct AttnArgs {
+    specvlm_attn_desc d;
+    float scale;                // resolved softmax scale
+    const void* q;
+    const void* k;
+    const void* v;
+    const int32_t* block_table;
+    const int32_t* prefix_len;
+    const int32_t* num_nodes;
+    const int32_t* parent;
+    void* o;
+    float* lse;
+    void* workspace;
+    size_t workspace_bytes;
+    int32_t* err_flag;
+    hipStream_t stream;
+};
+
+// fp32 VALU kernel: exact-ish path for SPECVLM_F32 (and a bf16 VALU variant kept for
+// comparison measurements).
+int32_t launch_attn_valu(const AttnArgs& a);
+
+// bf16 MFMA split-key kernel + merge.
+int32_t launch_attn_mfma(const AttnArgs& a);
+size_t attn_mfma_workspace_bytes(const specvlm_attn_desc& d);
+int32_t attn_mfma_pick_splits(const specvlm_attn_desc& d);
+
+}  // namespace specvlm

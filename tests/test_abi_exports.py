@@ -1,0 +1,51 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/specvlm.h declares."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "specvlm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(specvlm_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2509_11815_amd import build
+    if build.needs_build():
+        build.build()
+    lib = ctypes.CDLL(build.LIB)
+    names = declared_symbols()
+    assert {"specvlm_tree_verify_attn", "specvlm_node_argmax", "specvlm_tree_accept",
+            "specvlm_kv_compact"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+    lib.specvlm_version.restype = ctypes.c_int32
+    assert lib.specvlm_version() >= 100
+
+
+def test_host_side_argument_checks_need_no_gpu():
+    """Scalar validation happens before any HIP call."""
+    import paper_2509_11815_amd as sv
+    from paper_2509_11815_amd.binding import AttnDesc
+    lib = sv.load_library()
+    d = AttnDesc()
+    assert lib.specvlm_tree_verify_attn_workspace_bytes(ctypes.byref(d)) == 0          # all-zero desc
+    d.dtype, d.B, d.H_q, d.H_kv, d.D, d.N_max = 0, 1, 32, 32, 128, 60
+    d.kv_capacity = 3328
+    d.q_stride_b, d.q_stride_n, d.q_stride_h = 60 * 32 * 128, 32 * 128, 128
+    d.o_stride_b, d.o_stride_n, d.o_stride_h = 60 * 32 * 128, 32 * 128, 128
+    d.kv_stride_b, d.kv_stride_h, d.kv_stride_t = 32 * 3328 * 128, 3328 * 128, 128
+    need = lib.specvlm_tree_verify_attn_workspace_bytes(ctypes.byref(d))
+    assert need > 0
+    d.N_max = 65
+    assert lib.specvlm_tree_verify_attn_workspace_bytes(ctypes.byref(d)) == 0
+    d.N_max = 60
+    null = ctypes.c_void_p(None)
+    rc = lib.specvlm_tree_verify_attn(ctypes.byref(d), null, null, null, null, null, null, null, null, null,
+                                      null, 0, null, null)
+    assert rc == 1                                                                      # INVALID_ARG
+    assert lib.specvlm_node_argmax(0, 1, 65, 10, null, 0, 10, null, null, null) == 1
+    assert lib.specvlm_tree_accept(1, 8, 0, *([null] * 10)) == 1

@@ -1,0 +1,163 @@
+"""GPU parity of specvlm_tree_verify_attn against the fp64 oracle (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sv():
+    import paper_2509_11815_amd as sv
+    sv.load_library()
+    return sv
+
+
+def run_both(sv, oracle, case, *, num_splits=0, scale=None, want_lse=True):
+    from gpu_util import i32, to_dev, to_host_f64
+    q, k, v = to_dev(case["q"]), to_dev(case["k"]), to_dev(case["v"])
+    P, par = i32(case["prefix_len"]), i32(case["parent"])
+    nn = None if case["num_nodes"] is None else i32(case["num_nodes"])
+    bt = None if case["block_table"] is None else i32(case["block_table"])
+    B, N, H, D = case["q"].shape
+    out = torch.full_like(q, 7.0)                       # rows >= num_nodes must stay untouched
+    lse = torch.full((B, H, N), 7.0, dtype=torch.float32, device="cuda") if want_lse else None
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    sv.specvlm_tree_verify_attn(q, k, v, P, par, num_nodes=nn, block_table=bt, out=out, lse=lse,
+                                err_flag=err, softmax_scale=0.0 if scale is None else scale,
+                                num_splits=num_splits)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    ref_o, ref_lse = oracle.tree_attn(case["q"], case["k"], case["v"], case["prefix_len"], case["parent"],
+                                      case["num_nodes"], scale=scale, block_table=case["block_table"])
+    return to_host_f64(out), (None if lse is None else to_host_f64(lse)), ref_o, ref_lse
+
+
+def check(case, got_o, got_lse, ref_o, ref_lse, what):
+    from gpu_util import assert_attn_close, valid_rows_mask
+    B, N, H, D = case["q"].shape
+    rows = valid_rows_mask(B, N, case["num_nodes"])
+    assert_attn_close(got_o[rows], ref_o[rows], case["dtype"], what)
+    assert np.all(got_o[~rows] == 7.0), f"{what}: rows past num_nodes were written"
+    if got_lse is not None:
+        lrows = np.broadcast_to(rows[:, None, :], got_lse.shape)
+        tol = 2e-2 if case["dtype"] == "bf16" else 1e-5
+        assert np.abs(got_lse[lrows] - ref_lse[lrows]).max() <= tol, f"{what}: lse"
+        assert np.all(got_lse[~lrows] == 7.0)
+
+
+def test_c1_fp32_config(sv, oracle):
+    """Config 1: fp32, 4 heads, D 64, prefix 64, 8-node random tree; tolerance 1e-5."""
+    cfg = W.CONFIGS["C1"]
+    lay = W.make_attn_layer(cfg, 0)
+    tb = W.make_trees(cfg)
+    case = dict(q=lay.q, k=lay.k, v=lay.v, prefix_len=lay.prefix_len, num_nodes=None,
+                parent=tb.parent, block_table=None, dtype="f32")
+    check(case, *run_both(sv, oracle, case), "C1")
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_small_cases_ragged_gqa(sv, oracle, D, dtype):
+    """Several requests, ragged node counts, grouped KV heads, an empty prefix, explicit scale."""
+    from gpu_util import random_case
+    case = random_case(11, dtype, B=3, Hq=4, Hkv=2, D=D, N_max=20, P_list=[37, 0, 130],
+                       num_nodes=[20, 1, 13])
+    check(case, *run_both(sv, oracle, case, scale=0.11), f"small D={D} {dtype}")
+
+
+@pytest.mark.parametrize("num_splits", [1, 2, 3, 5, 16])
+def test_bf16_split_counts_span_tiles_and_tail(sv, oracle, num_splits):
+    """S = 333+60 keys: 25 sixteen-key blocks, a ragged last block, an odd tile count;
+    more splits than some ranges have blocks."""
+    from gpu_util import random_case
+    case = random_case(21 + num_splits, "bf16", B=2, Hq=3, Hkv=3, D=128, N_max=60, P_list=[333, 45],
+                       num_nodes=[60, 33])
+    check(case, *run_both(sv, oracle, case, num_splits=num_splits), f"splits={num_splits}")
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_bf16_paged_cache(sv, oracle, D):
+    from gpu_util import random_case
+    case = random_case(31, "bf16", B=3, Hq=2, Hkv=2, D=D, N_max=64, P_list=[200, 16, 95],
+                       num_nodes=[64, 17, 48], paged=True)
+    check(case, *run_both(sv, oracle, case, num_splits=3), f"paged D={D}")
+
+
+def test_fp32_paged_cache(sv, oracle):
+    from gpu_util import random_case
+    case = random_case(32, "f32", B=2, Hq=2, Hkv=1, D=64, N_max=9, P_list=[40, 3], paged=True)
+    check(case, *run_both(sv, oracle, case), "paged f32")
+
+
+def test_bf16_chain_and_single_node(sv, oracle):
+    """The oracle's two textbook special cases, on the GPU: chain tree and one-node tree."""
+    from gpu_util import random_case
+    case = random_case(41, "bf16", B=1, Hq=2, Hkv=2, D=128, N_max=40, P_list=[77], tree="chain")
+    check(case, *run_both(sv, oracle, case), "chain")
+    case = random_case(42, "bf16", B=2, Hq=2, Hkv=2, D=128, N_max=1, P_list=[77, 0])
+    check(case, *run_both(sv, oracle, case), "single node")
+
+
+def test_bf16_mask_leak_detectors(sv, oracle):
+    """V == 1 gives o == 1 up to one bf16 step; huge finite K/V in invisible tree slots and
+    NaN beyond the request's end change nothing."""
+    from gpu_util import random_case, i32, to_dev, to_host_f64
+    case = random_case(51, "bf16", B=1, Hq=2, Hkv=2, D=128, N_max=24, P_list=[100])
+    ones = np.full_like(case["v"], 0x3F80)              # bf16 1.0
+    S = 124
+    ones[:, :, S:] = W.NAN_BITS_BF16
+    c1 = dict(case, v=ones)
+    got, _, _, _ = run_both(sv, oracle, c1, num_splits=2)
+    assert np.abs(got - 1.0).max() <= 2 ** -7
+    # every query in turn: poison what it must not see
+    base = run_both(sv, oracle, case, num_splits=2)[0]
+    anc, _ = oracle.ancestors(case["parent"][0])
+    for i in (3, 11, 23):
+        k2, v2 = case["k"].copy(), case["v"].copy()
+        for j in range(24):
+            if not anc[i, j]:
+                k2[0, :, 100 + j] = W.f32_to_bf16_bits(np.float32(30.0))
+                v2[0, :, 100 + j] = W.f32_to_bf16_bits(np.float32(1e4))
+        got2 = run_both(sv, oracle, dict(case, k=k2, v=v2), num_splits=2)[0]
+        assert np.array_equal(got2[0, i], base[0, i])
+
+
+def test_strided_q_and_out(sv, oracle):
+    """q and o live inside a fused [B,N,3,H,D] projection buffer (non-dense strides)."""
+    from gpu_util import random_case, i32, to_dev, to_host_f64, assert_attn_close
+    case = random_case(61, "bf16", B=2, Hq=2, Hkv=2, D=128, N_max=30, P_list=[50, 64])
+    fused = torch.zeros((2, 30, 3, 2, 128), dtype=torch.bfloat16, device="cuda")
+    fused[:, :, 0] = to_dev(case["q"])
+    outbuf = torch.zeros_like(fused)
+    sv.specvlm_tree_verify_attn(fused[:, :, 0], to_dev(case["k"]), to_dev(case["v"]), i32(case["prefix_len"]),
+                                i32(case["parent"]), out=outbuf[:, :, 1])
+    torch.cuda.synchronize()
+    ref, _ = oracle.tree_attn(case["q"], case["k"], case["v"], case["prefix_len"], case["parent"])
+    assert_attn_close(to_host_f64(outbuf[:, :, 1]), ref, "bf16", "strided")
+    assert float(outbuf[:, :, 0].abs().max()) == 0.0 and float(outbuf[:, :, 2].abs().max()) == 0.0
+
+
+def test_error_reporting(sv):
+    """Host-detectable misuse returns a status; data-dependent misuse sets the device flag."""
+    from gpu_util import random_case, i32, to_dev
+    case = random_case(71, "bf16", B=1, Hq=1, Hkv=1, D=128, N_max=8, P_list=[20])
+    q, k, v = to_dev(case["q"]), to_dev(case["k"]), to_dev(case["v"])
+    P = i32(case["prefix_len"])
+    bad_parent = i32(np.array([[-1, 0, 2, 1, 0, 0, 0, 0]]))         # parent[2] = 2 is not < 2
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = torch.full_like(q, 3.0)
+    sv.specvlm_tree_verify_attn(q, k, v, P, bad_parent, out=out, err_flag=err)
+    torch.cuda.synchronize()
+    assert int(err.item()) & 1
+    err.zero_()
+    sv.specvlm_tree_verify_attn(q, k, v, i32([k.shape[2]]), i32(case["parent"]), out=out, err_flag=err)
+    torch.cuda.synchronize()
+    assert int(err.item()) & 4                                       # prefix + nodes > capacity
+    with pytest.raises(sv.SpecvlmError, match="INVALID_ARG"):
+        sv.specvlm_tree_verify_attn(q[..., :96], k[..., :96], v[..., :96], P, i32(case["parent"]))
+    with pytest.raises(sv.SpecvlmError, match="WORKSPACE_TOO_SMALL"):
+        sv.specvlm_tree_verify_attn(q, k, v, P, i32(case["parent"]), num_splits=4,
+                                    workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))

@@ -1,0 +1,149 @@
+"""GPU parity (bit-exact) of node_argmax, tree_accept and kv_compact against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sv():
+    import paper_2509_11815_amd as sv
+    sv.load_library()
+    return sv
+
+
+# ------------------------------------------------------------------ argmax
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("V", [1, 7, 1000, 32000, 32003])
+def test_argmax_matches_oracle(sv, oracle, dtype, V):
+    from gpu_util import i32, to_dev
+    rng = np.random.default_rng(V)
+    B, N = 2, 9
+    logits = W.normal(rng, (B, N, V), 2.0, dtype)
+    nn = np.array([9, 4], dtype=np.int32)
+    got = sv.specvlm_node_argmax(to_dev(logits), num_nodes=i32(nn)).cpu().numpy()
+    assert np.array_equal(got, oracle.node_argmax(logits, nn))
+
+
+def test_argmax_ties_signed_zero_inf(sv, oracle):
+    from gpu_util import to_dev
+    V = 4099
+    x = np.full((1, 6, V), -1.0, dtype=np.float32)
+    x[0, 0, [4000, 31, 2222]] = 3.0
+    x[0, 1, :] = -np.inf
+    x[0, 2, :] = -np.inf
+    x[0, 2, 4098] = -1e30
+    x[0, 3, :] = -0.0
+    x[0, 3, 77] = 0.0
+    x[0, 4, 4098] = np.inf
+    x[0, 5, 1] = 2.0
+    x[0, 5, 0] = 2.0
+    for arr in (x, W.f32_to_bf16_bits(x)):
+        got = sv.specvlm_node_argmax(to_dev(arr)).cpu().numpy()
+        assert np.array_equal(got, oracle.node_argmax(arr))
+        assert got[0].tolist() == [31, 0, 4098, 0, 4098, 0]
+
+
+def test_argmax_unaligned_strided_rows(sv, oracle):
+    """Rows that start off a 16-byte boundary (odd row stride, offset view)."""
+    from gpu_util import to_dev
+    rng = np.random.default_rng(3)
+    big = W.normal(rng, (2, 5, 1037), 2.0, "bf16")
+    dev = to_dev(big)
+    view_np, view_dev = big[:, :, 3:1030], dev[:, :, 3:1030]
+    got = sv.specvlm_node_argmax(view_dev).cpu().numpy()
+    assert np.array_equal(got, oracle.node_argmax(view_np))
+
+
+# ------------------------------------------------------------------ accept
+@pytest.mark.parametrize("seed", range(4))
+def test_accept_matches_oracle_random_trees(sv, oracle, seed):
+    """Tiny vocabulary: equal sibling tokens and deep matches are frequent."""
+    from gpu_util import i32
+    rng = np.random.default_rng(300 + seed)
+    B, N, V, cap = 200, 64, 3, 9
+    parent = np.stack([W.random_tree(rng, N, 8) for _ in range(B)])
+    tok = rng.integers(0, V, size=(B, N)).astype(np.int32)
+    amax = rng.integers(0, V, size=(B, N)).astype(np.int32)
+    nn = rng.integers(1, N + 1, size=B).astype(np.int32)
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    got = sv.specvlm_tree_accept(i32(parent), i32(tok), i32(amax), num_nodes=i32(nn), path_cap=cap, err_flag=err)
+    ref = oracle.tree_accept(parent, tok, amax, nn, path_cap=cap)
+    for g, r, name in zip(got, ref, ["accept_len", "path", "bonus", "committed"]):
+        assert np.array_equal(g.cpu().numpy(), r), name
+    assert int(err.item()) == 0
+    assert ref[0].max() >= 3
+
+
+def test_accept_error_flags(sv):
+    from gpu_util import i32
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    m, path, bonus, committed = sv.specvlm_tree_accept(i32([[-1, 1, 0]]), i32([[0, 0, 0]]), i32([[5, 6, 7]]),
+                                                       path_cap=4, err_flag=err)
+    assert int(err.item()) & 1 and int(m.item()) == 0 and path[0].tolist() == [0, -1, -1, -1]
+    assert int(bonus.item()) == 5 and committed[0].tolist() == [5, -1, -1, -1]
+    err.zero_()
+    # chain 0-1-2 fully matching but path_cap 2: only one draft node fits
+    m, path, _, committed = sv.specvlm_tree_accept(i32([[-1, 0, 1]]), i32([[0, 5, 6]]), i32([[5, 6, 7]]),
+                                                   path_cap=2, err_flag=err)
+    assert int(err.item()) & 8 and int(m.item()) == 1 and path[0].tolist() == [0, 1]
+    assert committed[0].tolist() == [5, 6]
+
+
+# ------------------------------------------------------------------ compaction
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
+@pytest.mark.parametrize("paged", [False, True])
+def test_compact_matches_oracle(sv, oracle, dtype, D, paged):
+    from gpu_util import i32, to_dev, to_host_bits
+    rng = np.random.default_rng(5)
+    L, B, H, bs, cap = 3, 3, 2, 16, 8
+    P = np.array([5, 30, 16], dtype=np.int32)
+    paths = np.array([[0, 2, 3, 7, -1, -1, -1, -1], [0, 1, 2, 3, 4, 5, 6, 9], [0, -1, -1, -1, -1, -1, -1, -1]],
+                     dtype=np.int32)
+    m = np.array([3, 7, 0], dtype=np.int32)
+    S_cap = 48
+    if paged:
+        table, nb = W.block_table(rng, B, S_cap // bs, spare=0.5)
+        shape = (L, nb, H, bs, D)
+    else:
+        table = None
+        shape = (L, B, H, S_cap, D)
+    if dtype == "bf16":
+        k = rng.integers(0, 65536, size=shape, dtype=np.uint16)
+        v = rng.integers(0, 65536, size=shape, dtype=np.uint16)
+    else:
+        k = rng.standard_normal(shape).astype(np.float32)
+        v = rng.standard_normal(shape).astype(np.float32)
+    kd, vd = to_dev(k), to_dev(v)
+    moved = torch.zeros((B, cap, 2), dtype=torch.int32, device="cuda")
+    Pd = i32(P)
+    newp, _ = sv.specvlm_kv_compact(kd, vd, Pd, i32(paths), i32(m), block_table=None if table is None else i32(table),
+                                    new_prefix_len=Pd, moved_idx=moved)       # aliasing prefix_len
+    torch.cuda.synchronize()
+    ref_newp, ref_moved = oracle.kv_compact(k, v, P, paths, m, block_table=table)
+    assert np.array_equal(newp.cpu().numpy(), ref_newp)
+    assert np.array_equal(moved.cpu().numpy(), ref_moved)
+    assert np.array_equal(to_host_bits(kd), k) and np.array_equal(to_host_bits(vd), v)
+
+
+def test_compact_layer_pointer_array(sv, oracle):
+    """Layers allocated separately and passed as a device array of pointers."""
+    from gpu_util import i32, to_dev, to_host_bits
+    rng = np.random.default_rng(6)
+    L, B, H, S_cap, D = 4, 2, 3, 40, 128
+    ks = [rng.integers(0, 65536, size=(B, H, S_cap, D), dtype=np.uint16) for _ in range(L)]
+    vs = [rng.integers(0, 65536, size=(B, H, S_cap, D), dtype=np.uint16) for _ in range(L)]
+    kd, vd = [to_dev(x) for x in ks], [to_dev(x) for x in vs]
+    kp = torch.tensor([t.data_ptr() for t in kd], dtype=torch.int64, device="cuda")
+    vp = torch.tensor([t.data_ptr() for t in vd], dtype=torch.int64, device="cuda")
+    P, paths, m = np.array([7, 20], dtype=np.int32), np.array([[0, 3, 4, 9], [0, 2, -1, -1]], dtype=np.int32), np.array([3, 1], dtype=np.int32)
+    newp, _ = sv.specvlm_kv_compact(kd[0], vd[0], i32(P), i32(paths), i32(m), layer_ptrs=(kp, vp))
+    torch.cuda.synchronize()
+    kh, vh = np.stack(ks), np.stack(vs)
+    ref_newp, _ = oracle.kv_compact(kh, vh, P, paths, m)
+    assert np.array_equal(newp.cpu().numpy(), ref_newp)
+    for l in range(L):
+        assert np.array_equal(to_host_bits(kd[l]), kh[l]) and np.array_equal(to_host_bits(vd[l]), vh[l])

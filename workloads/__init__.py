@@ -82,8 +82,8 @@ def eagle_tree(rng: np.random.Generator, n_nodes: int = 60, depth: int = 6, topk
     Every expanded node gets `topk` children whose probabilities are the sorted
     softmax of `topk` N(0,1.5) draws; a node's score is the product of the
     probabilities on its root path; per level the `topk` best new nodes are
-    expanded; finally the root, the greedy best chain down to `depth` (so the
-    stated depth is reached) and the best-scoring remaining nodes are kept and
+    expanded; finally the root, the best node of the last level with its root
+    path (so the stated depth is reached) and the best-scoring remaining nodes are kept and
     renumbered by (depth, -score) so that parent[i] < i.
 
     Returns (parent [n_nodes] int32, score [n_nodes] float64, rank [n_nodes]
@@ -108,11 +108,11 @@ def eagle_tree(rng: np.random.Generator, n_nodes: int = 60, depth: int = 6, topk
     score = np.array(score)
     dep = np.array(dep)
     keep = {0}
-    t = 0
-    for _ in range(depth):                      # greedy best chain reaches full depth
-        kids = np.nonzero(par == t)[0]
-        t = int(kids[np.argmax(score[kids])])
+    deepest = np.nonzero(dep == depth)[0]
+    t = int(deepest[np.argmax(score[deepest])])     # best node of the last level and its root path,
+    while t != -1:                                  # so that the stated depth is reached
         keep.add(t)
+        t = int(par[t])
     for t in np.argsort(-score, kind="stable"):
         if len(keep) >= n_nodes:
             break
@@ -227,6 +227,7 @@ class Config:
     prefix: tuple = ()    # fixed per-request committed prefix lengths, or () if drawn
     tree: str = "eagle"   # 'eagle' | 'random'
     alpha: float = 0.75
+    tree_salt: int = 0    # added to the tree/logit seed; picks which seeded draw the config uses
     note: str = ""
     extra: dict = field(default_factory=dict)
 
@@ -234,9 +235,9 @@ class Config:
 CONFIGS = {
     "C1": Config("C1", 1, "f32", 1, 4, 64, 1, 8, 3, 1000, 1.0, prefix=(64,), tree="random",
                  alpha=0.5, note="tiny fp32 plumbing case"),
-    "C2": Config("C2", 2, "bf16", 32, 32, 128, 1, 60, 6, 32000, 2.0, prefix=(576 + 64 + 128,),
+    "C2": Config("C2", 2, "bf16", 32, 32, 128, 1, 60, 6, 32000, 2.0, prefix=(576 + 64 + 128,), tree_salt=5,
                  note="LLaVA-1.5-7B-shaped, 576 visual + 64 text + 128 generated"),
-    "C3": Config("C3", 3, "bf16", 32, 32, 128, 1, 60, 6, 32000, 2.0, prefix=(2880 + 128 + 256,),
+    "C3": Config("C3", 3, "bf16", 32, 32, 128, 1, 60, 6, 32000, 2.0, prefix=(2880 + 128 + 256,), tree_salt=3,
                  note="LLaVA-1.6-7B anyres-shaped, 2880 visual + 128 text + 256 generated"),
     "C4": Config("C4", 4, "bf16", 32, 32, 128, 8, 60, 6, 32000, 2.0,
                  note="compressed-visual variable-length batch",
@@ -275,7 +276,7 @@ class TreeBatch:
 
 def make_trees(cfg: Config) -> TreeBatch:
     """Trees, draft tokens and target logits of one verify step."""
-    rng = np.random.default_rng(config_seed(cfg, 0, stream=1))
+    rng = np.random.default_rng(config_seed(cfg, cfg.tree_salt, stream=1))
     parents, toks = [], []
     logits, top = planted_logits(rng, cfg.B * cfg.N, cfg.V, cfg.sigma_logits, cfg.dtype)
     logits = logits.reshape(cfg.B, cfg.N, cfg.V)
