@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification hot path on one MI355X.
+
+A "step" is one verify step of the target model over a draft token tree: L layers of
+tree-masked attention, then per-node vocab argmax, the greedy acceptance walk and KV
+compaction of the accepted path -- all four C-ABI calls of libspecvlm, inputs resident in HBM.
+Default workload: the LLaVA-1.6-7B anyres-shaped configuration (2880 visual + 128 text + 256
+generated prefix tokens, 60-node tree, 32 layers x 32 heads x 128, bf16), synthetic data.
+
+Prints ONE JSON line: whole-step KV-cache streaming rate (algorithmic K+V bytes of all layers
+divided by the step time), verify steps/s, the roofline of the attention kernel and the fp64
+CPU oracle timed on this host on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/),
+# keyed by workload; None until measured.
+MEASURED_TRAFFIC = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5"])
+    ap.add_argument("--splits", type=int, default=0, help="key-range splits per (request, head); 0 = library default")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU oracle baseline leg")
+    ap.add_argument("--attn-only", action="store_true", help="profile helper: run only the attention launches")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2509_11815_amd as sv
+    import workloads as W
+
+    sv.load_library()                       # fails loudly when the HIP library is missing
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = W.CONFIGS[args.workload]
+    L, B, H, D, N = cfg.L, cfg.B, cfg.H, cfg.D, cfg.N
+    P = W.prefix_lengths(cfg)
+    S = P.astype(np.int64) + N
+    path_cap = cfg.depth + 1
+    torch.manual_seed(W.config_seed(cfg))
+
+    # ---- synthetic inputs, resident in HBM; every layer has its own K/V memory -------------
+    q = torch.randn((L, B, N, H, D), dtype=torch.bfloat16, device=dev)
+    if cfg.paged:
+        bs = cfg.block_size
+        bpr = W.round_up(int(S.max()), bs) // bs
+        table_np, nb = W.block_table(np.random.default_rng(W.config_seed(cfg, 0, 3)), B, bpr)
+        kshape = (L, nb, H, bs, D)
+        table = torch.from_numpy(table_np).to(dev)
+    else:
+        kshape = (L, B, H, W.round_up(int(S.max()), 16), D)
+        table = None
+    k = torch.empty(kshape, dtype=torch.bfloat16, device=dev)
+    v = torch.empty(kshape, dtype=torch.bfloat16, device=dev)
+    for l in range(L):                      # N(0,1) like the parity inputs
+        k[l].normal_()
+        v[l].normal_()
+    tb = W.make_trees(cfg)
+    parent = torch.from_numpy(tb.parent).to(dev)
+    draft_tok = torch.from_numpy(tb.draft_tok).to(dev)
+    logits = torch.from_numpy(tb.logits.view(np.int16)).to(dev).view(torch.bfloat16)
+    prefix_len = torch.from_numpy(P).to(dev)
+
+    out = torch.empty_like(q)
+    err = torch.zeros(1, dtype=torch.int32, device=dev)
+    desc = sv.binding.make_attn_desc(q[0], k[0], out[0], block_table=table, num_splits=args.splits)
+    wbytes = sv.specvlm_tree_verify_attn_workspace_bytes(desc)
+    workspace = torch.empty(max(wbytes, 256), dtype=torch.uint8, device=dev)
+    amax = torch.empty((B, N), dtype=torch.int32, device=dev)
+    acc_out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty((B, path_cap), dtype=torch.int32, device=dev),
+               torch.empty(B, dtype=torch.int32, device=dev), torch.empty((B, path_cap), dtype=torch.int32, device=dev))
+    new_prefix = torch.empty(B, dtype=torch.int32, device=dev)
+
+    def attn_layers():
+        for l in range(L):
+            sv.specvlm_tree_verify_attn(q[l], k[l], v[l], prefix_len, parent, block_table=table, out=out[l],
+                                        workspace=workspace, err_flag=err, desc=desc)
+
+    def sample_and_compact():
+        sv.specvlm_node_argmax(logits, out=amax)
+        sv.specvlm_tree_accept(parent, draft_tok, amax, err_flag=err, out=acc_out)
+        # the prefix length is NOT advanced between steps, so every step sees the same workload
+        sv.specvlm_kv_compact(k, v, prefix_len, acc_out[1], acc_out[0], block_table=table, new_prefix_len=new_prefix)
+
+    def step():
+        attn_layers()
+        sample_and_compact()
+
+    def make_runner(fn):
+        if args.no_graph:
+            return fn
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return g.replay
+
+    def timed(run, iters, warmup):
+        for _ in range(warmup):
+            run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters          # ms per iteration
+
+    if args.attn_only:
+        run_attn = make_runner(attn_layers)
+        ms = timed(run_attn, args.steps, args.warmup)
+        print(json.dumps({"attn_only_ms_per_step": ms, "ms_per_layer_call": ms / L}))
+        return
+
+    run_step = make_runner(step)
+    ms_step = timed(run_step, args.steps, args.warmup)
+    run_attn = make_runner(attn_layers)
+    ms_attn = timed(run_attn, args.steps, args.warmup)
+    run_tail = make_runner(sample_and_compact)
+    ms_tail = timed(run_tail, args.steps, args.warmup)
+    assert int(err.item()) == 0, "device error flag set"
+
+    kv_bytes_layer = W.kv_bytes_per_layer(cfg)
+    kv_bytes_step = kv_bytes_layer * L
+    value = kv_bytes_step / (ms_step * 1e-3) / 1e9
+    attn_launch_us = ms_attn * 1e3 / L
+    achieved = kv_bytes_layer / (attn_launch_us * 1e-6) / 1e9
+
+    result = {
+        "metric": "tree-verify attn KV GB/s (% HBM peak); verify steps/s at 2880-token prefix",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.note}; B={B}, L={L}, H={H}, D={D}, prefix={P.tolist()}, "
+                               f"tree nodes={N}, depth={cfg.depth}, vocab={cfg.V}, paged={cfg.paged}",
+                   "launch": "HIP graph replay of one whole step" if not args.no_graph else "eager launches",
+                   "num_splits": sv.specvlm_tree_verify_attn_num_splits(desc),
+                   "accept_len": acc_out[0].tolist()},
+        "verify_steps_per_s": round(1e3 / ms_step, 1),
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "breakdown_ms": {"attention_all_layers": round(ms_attn, 5), "argmax_accept_compact": round(ms_tail, 5)},
+        "roofline": {"kernel": "specvlm_tree_verify_attn (split-key MFMA kernel + split merge), one layer",
+                     "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "algorithmic_bytes_per_launch": kv_bytes_layer,
+                     "avg_launch_us": round(attn_launch_us, 3),
+                     "traffic": MEASURED_TRAFFIC.get(cfg.name)},
+    }
+
+    # ---- CPU baseline: the fp64 oracle as it stands, on this host, on a bounded sample ------
+    if not args.skip_cpu:
+        import oracle
+        oracle.build()
+        q0 = q[0].view(torch.int16).cpu().numpy().view(np.uint16)
+        k0 = k[0].view(torch.int16).cpu().numpy().view(np.uint16)
+        v0 = v[0].view(torch.int16).cpu().numpy().view(np.uint16)
+        t0 = time.perf_counter()
+        oracle.tree_attn(q0, k0, v0, P, tb.parent, block_table=None if table is None else table_np)
+        t_layer = time.perf_counter() - t0
+        n_layers = int(min(L, max(1, round(15.0 / max(t_layer, 1e-3)))))
+        t0 = time.perf_counter()
+        for _ in range(n_layers):
+            oracle.tree_attn(q0, k0, v0, P, tb.parent, block_table=None if table is None else table_np)
+        r_amax = oracle.node_argmax(tb.logits)
+        r_m, r_path, _, _ = oracle.tree_accept(tb.parent, tb.draft_tok, r_amax, path_cap=path_cap)
+        kk, vv = k0[None].copy(), v0[None].copy()
+        for _ in range(n_layers):
+            oracle.kv_compact(kk, vv, P, r_path, r_m, block_table=None if table is None else table_np)
+        t_cpu = time.perf_counter() - t0
+        result["cpu_baseline"] = {
+            "value": round(kv_bytes_layer * n_layers / t_cpu / 1e9, 4), "unit": "GB/s",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{n_layers} of {L} layers of attention and compaction (one layer's tensors reused) + "
+                      f"argmax + accept, {t_cpu:.2f} s; a full step would take about {t_cpu * L / n_layers:.1f} s",
+            "host_cpus": os.cpu_count()}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -97,6 +97,13 @@ int32_t specvlm_last_hip_error(void);
 size_t specvlm_tree_verify_attn_workspace_bytes(const specvlm_attn_desc *desc);
 
 /*
+ * Number of key-range splits per (request, head) specvlm_tree_verify_attn will use for
+ * `desc` (desc->num_splits when that is positive, otherwise the library's choice for the
+ * shape).  Returns 0 when desc is invalid, 1 for SPECVLM_F32 (no split path).
+ */
+int32_t specvlm_tree_verify_attn_num_splits(const specvlm_attn_desc *desc);
+
+/*
  * Tree-masked verification attention for ONE layer (Sec. 3.1 "verifies ... in a
  * single forward pass", Sec. 4.1 "tree attention"; Sec. 3.2: the whole KV cache
  * is streamed from HBM once per step).  For request b, query head h and tree

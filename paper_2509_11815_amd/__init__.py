@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     specvlm_node_argmax,
     specvlm_tree_accept,
     specvlm_tree_verify_attn,
+    specvlm_tree_verify_attn_num_splits,
     specvlm_tree_verify_attn_workspace_bytes,
     specvlm_version,
 )

@@ -18,6 +18,7 @@ STATUS = {0: "OK", 1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE_TOO_SMALL",
 ERR_BITS = {1: "BAD_PARENT", 2: "BAD_NUM_NODES", 4: "BAD_LENGTH", 8: "PATH_TOO_LONG", 16: "BAD_BLOCK"}
 
 EXPORTS = ["specvlm_version", "specvlm_last_hip_error", "specvlm_tree_verify_attn_workspace_bytes",
+           "specvlm_tree_verify_attn_num_splits",
            "specvlm_tree_verify_attn", "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_kv_compact"]
 
 
@@ -55,6 +56,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.specvlm_last_hip_error.restype = i32
     L.specvlm_tree_verify_attn_workspace_bytes.restype = ctypes.c_size_t
     L.specvlm_tree_verify_attn_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc)]
+    L.specvlm_tree_verify_attn_num_splits.restype = i32
+    L.specvlm_tree_verify_attn_num_splits.argtypes = [ctypes.POINTER(AttnDesc)]
     L.specvlm_tree_verify_attn.restype = i32
     L.specvlm_tree_verify_attn.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 9 + [vp, ctypes.c_size_t, vp, vp]
     L.specvlm_node_argmax.restype = i32
@@ -137,6 +140,10 @@ def specvlm_tree_verify_attn_workspace_bytes(desc: AttnDesc) -> int:
     return int(lib().specvlm_tree_verify_attn_workspace_bytes(ctypes.byref(desc)))
 
 
+def specvlm_tree_verify_attn_num_splits(desc: AttnDesc) -> int:
+    return int(lib().specvlm_tree_verify_attn_num_splits(ctypes.byref(desc)))
+
+
 def specvlm_tree_verify_attn(q, k_cache, v_cache, prefix_len, parent, *, num_nodes=None, block_table=None,
                              out=None, lse=None, workspace=None, err_flag=None, softmax_scale=0.0,
                              num_splits=0, desc=None, stream=None):
@@ -175,14 +182,20 @@ def specvlm_node_argmax(logits, *, num_nodes=None, out=None, stream=None):
     return out
 
 
-def specvlm_tree_accept(parent, draft_tok, amax, *, num_nodes=None, path_cap=8, err_flag=None, stream=None):
-    """Returns (accept_len [B], path [B,path_cap], bonus_tok [B], committed_tok [B,path_cap])."""
+def specvlm_tree_accept(parent, draft_tok, amax, *, num_nodes=None, path_cap=8, err_flag=None, out=None,
+                        stream=None):
+    """Returns (accept_len [B], path [B,path_cap], bonus_tok [B], committed_tok [B,path_cap]);
+    `out` may supply these four int32 device tensors."""
     B, N_max = parent.shape
     dev = parent.device
-    accept_len = torch.empty(B, dtype=torch.int32, device=dev)
-    path = torch.empty((B, path_cap), dtype=torch.int32, device=dev)
-    bonus = torch.empty(B, dtype=torch.int32, device=dev)
-    committed = torch.empty((B, path_cap), dtype=torch.int32, device=dev)
+    if out is not None:
+        accept_len, path, bonus, committed = out
+        path_cap = path.shape[1]
+    else:
+        accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+        path = torch.empty((B, path_cap), dtype=torch.int32, device=dev)
+        bonus = torch.empty(B, dtype=torch.int32, device=dev)
+        committed = torch.empty((B, path_cap), dtype=torch.int32, device=dev)
     rc = lib().specvlm_tree_accept(B, N_max, path_cap, _ptr(_dev_i32(parent, "parent")),
                                    _ptr(_dev_i32(draft_tok, "draft_tok")), _ptr(_dev_i32(amax, "amax")),
                                    _ptr(_dev_i32(num_nodes, "num_nodes")), _ptr(accept_len), _ptr(path),

@@ -59,6 +59,12 @@ size_t specvlm_tree_verify_attn_workspace_bytes(const specvlm_attn_desc* desc) {
     return attn_mfma_workspace_bytes(*desc);
 }
 
+int32_t specvlm_tree_verify_attn_num_splits(const specvlm_attn_desc* desc) {
+    if (!desc || check_attn_desc(*desc)) return 0;
+    if (desc->dtype == SPECVLM_F32 || desc->num_splits == 1000) return 1;
+    return attn_mfma_pick_splits(*desc);
+}
+
 int32_t specvlm_tree_verify_attn(const specvlm_attn_desc* desc, const void* q_dev, const void* k_cache_dev,
                                  const void* v_cache_dev, const int32_t* block_table_dev,
                                  const int32_t* prefix_len_dev, const int32_t* num_nodes_dev,
