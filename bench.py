@@ -91,7 +91,7 @@ def main():
     err = torch.zeros(1, dtype=torch.int32, device=dev)
     desc = sv.binding.make_attn_desc(q[0], k[0], out[0], block_table=table, num_splits=args.splits)
     wbytes = sv.specvlm_tree_verify_attn_workspace_bytes(desc)
-    workspace = torch.empty(max(wbytes, 256), dtype=torch.uint8, device=dev)
+    workspace = torch.zeros(max(wbytes, 256), dtype=torch.uint8, device=dev)
     amax = torch.empty((B, N), dtype=torch.int32, device=dev)
     acc_out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty((B, path_cap), dtype=torch.int32, device=dev),
                torch.empty(B, dtype=torch.int32, device=dev), torch.empty((B, path_cap), dtype=torch.int32, device=dev))

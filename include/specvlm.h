@@ -89,10 +89,12 @@ int32_t specvlm_version(void);
 int32_t specvlm_last_hip_error(void);
 
 /*
- * Scratch bytes specvlm_tree_verify_attn needs for `desc` (split-key partial
- * results).  Returns 0 when desc is invalid.  The workspace is device memory,
- * 256-byte aligned, used only during the call's kernels; its contents need no
- * initialisation and are garbage afterwards.
+ * Scratch bytes specvlm_tree_verify_attn needs for `desc` (arrival counters and split-key
+ * partial results; 0 when the shape needs none).  Returns 0 when desc is invalid.  The
+ * workspace is device memory, 256-byte aligned.  It must be ZERO-FILLED ONCE after
+ * allocation; every call leaves its counter words zero again, so the same workspace can
+ * be reused by later calls (of any shape it is large enough for) without clearing.  Two
+ * calls that may run concurrently need separate workspaces.
  */
 size_t specvlm_tree_verify_attn_workspace_bytes(const specvlm_attn_desc *desc);
 

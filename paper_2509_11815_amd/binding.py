@@ -157,7 +157,7 @@ def specvlm_tree_verify_attn(q, k_cache, v_cache, prefix_len, parent, *, num_nod
         raise ValueError("K and V caches must share one geometry")
     need = specvlm_tree_verify_attn_workspace_bytes(desc)
     if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)   # zero-filled once, as the ABI asks
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = lib().specvlm_tree_verify_attn(
         ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(_dev_i32(block_table, "block_table")),

@@ -160,4 +160,4 @@ def test_error_reporting(sv):
         sv.specvlm_tree_verify_attn(q[..., :96], k[..., :96], v[..., :96], P, i32(case["parent"]))
     with pytest.raises(sv.SpecvlmError, match="WORKSPACE_TOO_SMALL"):
         sv.specvlm_tree_verify_attn(q, k, v, P, i32(case["parent"]), num_splits=4,
-                                    workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+                                    workspace=torch.zeros(256, dtype=torch.uint8, device="cuda"))
