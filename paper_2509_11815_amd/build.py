@@ -17,6 +17,9 @@ def hipcc_command(out: str = LIB) -> list[str]:
             "-I" + INCLUDE, "-I" + CSRC,
             # compiler-generated packed fp32 ops are switched off on the test machines
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            # keep MFMA accumulators in architectural VGPRs: the attention kernel rescales and
+            # converts them with VALU ops, and AGPR copies would dominate its inner loop
+            "-mllvm", "-amdgpu-mfma-vgpr-form",
             "-o", out] + [os.path.join(CSRC, s) for s in SOURCES]
 
 

@@ -3,30 +3,31 @@
 // The step is bound by streaming K and V once from HBM (SpecVLM Sec. 3.2); all (up to 64)
 // tree queries of a head share that single pass.  Work decomposition:
 //
-//   grid      one workgroup (4 wavefronts) per (request, query head, key-range split)
-//   tiles     the workgroup walks its key range in 64-key tiles.  All 256 threads fetch a
-//             tile with fully coalesced 16-byte loads (one 256-byte K or V row per 16
-//             lanes), two tiles ahead, into registers, and park it in a double-buffered
-//             LDS stage from which the four wavefronts read it: every K/V byte leaves HBM
-//             and L2 exactly once
-//   queries   wavefront w owns query rows 16w..16w+15 for the whole key range, so its
-//             accumulator is only 16 x D and needs no merge inside the workgroup
-//   QK^T      S^T[64 keys x 16 q] = K . Q^T with v_mfma_f32_16x16x32_bf16; the K stage is
-//             XOR-swizzled so the operand reads (16 different rows per 16 lanes) are free
-//             of bank conflicts
+//   grid      one workgroup (4 wavefronts) per (request, query head, split); the 4*splits
+//             wavefronts of a (request, head) are independent "streams": stream s owns the
+//             32-key tiles s, s + 4*splits, ... of that head and ALL 64 query rows, so a
+//             K/V byte is fetched by exactly one wavefront, and the main loop has no
+//             workgroup barrier
+//   fetch     every stream keeps a private two-slot LDS ring and fills it with direct-to-LDS
+//             loads (global_load_lds_dwordx4: no registers are tied up by bytes in flight);
+//             one load instruction moves four whole 256-byte rows, fully coalesced.  The
+//             next tile is always in flight while the current one is consumed; completion
+//             is tracked by hand with s_waitcnt vmcnt
+//   QK^T      S^T[32 keys x 64 q] = K . Q^T with v_mfma_f32_16x16x32_bf16; the lanes fetch
+//             K granules in XOR-swizzled order so that the operand reads (16 different rows
+//             per 16 lanes) are free of LDS bank conflicts; Q is a swizzled LDS tile too
 //   softmax   online (running max / sum per query) in fp32 on the S^T fragments: a lane
-//             holds one query and 16 keys, so row statistics need two cross-lane steps,
-//             and exp2(S^T) packed to bf16 is already the B operand of the next MFMA
-//   PV        O^T[D x 16 q] += V^T . P^T; V rows are read from LDS as rows and transposed
+//             holds one query and 8 keys, so row statistics need two cross-lane steps, and
+//             exp2(S^T) packed to bf16 is already the B operand of the next MFMA
+//   PV        O^T[D x 64 q] += V^T . P^T; V rows are read from LDS as rows and transposed
 //             two bytes at a time with v_perm_b32 (the contraction index may be permuted
 //             freely, so an operand's "8 consecutive k" are 8 rows of one column)
-//   masks     prefix keys need none; only tiles touching the tree region or the end of the
-//             range test the per-query ancestor bit mask (select, never multiply: masked
-//             slots may hold anything)
-//   splits    fp32 partials go to a lane-major workspace; the last workgroup of a
-//             (request, head) to finish -- found with a ticket counter -- merges them
-#include <stdlib.h>
-
+//   masks     prefix keys need none; only tiles touching the tree region or the request's
+//             end test the per-query ancestor bit mask (select, never multiply)
+//   merge     the 4 streams of a workgroup are merged through LDS (one round, the rings
+//             are free by then); the workgroup's partial goes, as bf16, to a lane-major
+//             workspace with write-through stores, and the last workgroup of a
+//             (request, head) to arrive -- found with a ticket counter -- merges the splits
 #include "common.hpp"
 
 namespace specvlm {
@@ -40,10 +41,12 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
-constexpr int kQRows = 64;          // padded query rows: 16 per wavefront
-constexpr int kTile = 64;           // keys per tile
+constexpr int kQRows = 64;          // padded query rows: 4 MFMA column blocks of 16
+constexpr int kTile = 32;           // keys per tile
+constexpr int kSlots = 2;           // ring depth per stream
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kTau = 8.0f;        // log2 of how far a probability may exceed 1 before the reference max moves
 constexpr size_t kCounterAlign = 256;
 
 struct MfmaParams {
@@ -57,9 +60,8 @@ struct MfmaParams {
     const int32_t *prefix_len, *num_nodes, *parent;
     int32_t* err_flag;
     int32_t* ws_cnt;            // [B*H_q] arrival tickets, zero between calls
-    float* ws_acc;              // [B*H_q*num_splits][4 qb][NT][64 lanes] f32x4
+    float* ws_acc;              // [B*H_q*num_splits][4 qb][NT/2][64 lanes] 16-byte vectors of packed bf16
     float* ws_ml;               // [B*H_q*num_splits][64 q][2] (max, sum)
-    int dbg;
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
@@ -69,6 +71,27 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// 16 bytes per lane from global memory straight into LDS at lds_dst + 16*lane (the LDS base
+// travels in M0).  The compiler does not see the LDS write: every consumer sits behind
+// wait_vmcnt<>() below, which is also a compiler memory barrier.
+__device__ __forceinline__ void dma16(const void* gsrc, uint32_t lds_dst) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gsrc), "s"(lds_dst)
+                 : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+// Write-through (device-coherent) 16-byte store for data that another workgroup, possibly
+// behind another L2, reads in the same kernel.
+__device__ __forceinline__ void store16_coherent(void* dst, u32x4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(dst), "v"(v) : "memory");
+}
 
 // Writes one wavefront's 16 query rows: out[t][i] = O^T[d = NT*(4g+i) + t][q], unnormalised.
 template <int NT>
@@ -96,12 +119,17 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     constexpr int NC = D / 32;                 // QK^T contraction steps of 32
     constexpr int NT = D / 16;                 // PV output row blocks (O^T rows = head dim)
     constexpr int ROWG = D / 8;                // 16-byte granules per K/V row
-    constexpr int RPL = kThreads / ROWG;       // rows covered by one load of the workgroup (16 or 32)
-    constexpr int LD = kTile / RPL;            // loads per thread per tile, for K and again for V
-    constexpr int kStageBytes = kTile * D * 2; // one K (or V) tile
+    constexpr int RPI = 64 / ROWG;             // rows moved by one wavefront load (4 or 8)
+    constexpr int KLD = kTile / RPI;           // load instructions per tile, for K and again for V
+    constexpr int kTileBytes = kTile * D * 2;  // one K (or V) tile
+    constexpr int kSlotBytes = 2 * kTileBytes; // K tile then V tile
+    constexpr int kRingBytes = kSlots * kSlotBytes;
+    static_assert(kWaves * kRingBytes >= kWaves * 3 * NT * 64 * 16, "merge scratch must fit in the rings");
 
-    __shared__ __attribute__((aligned(16))) unsigned char s_k[2][kStageBytes];
-    __shared__ __attribute__((aligned(16))) unsigned char s_v[2][kStageBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char s_ring[kWaves * kRingBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char s_q[kQRows * D * 2];
+    __shared__ float s_m[kWaves][kQRows];
+    __shared__ float s_l[kWaves][kQRows];
     __shared__ int s_par[SPECVLM_MAX_NODES];
     __shared__ int s_flag;
 
@@ -113,7 +141,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     const int bh = work / p.num_splits;
     const int h = bh % p.H_q, b = bh / p.H_q;
     const int hk = h / p.group;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
 
     int err = 0;
@@ -122,6 +151,51 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     if (n < 1 || n > p.N_max) err |= SPECVLM_ERR_BAD_NUM_NODES;
     n = min(max(n, 1), p.N_max);
     if (P < 0 || P + n > p.g.capacity) err |= SPECVLM_ERR_BAD_LENGTH;
+    const int S = P + n;
+    const int ntile = (S + kTile - 1) / kTile;                       // 32-key tiles of this request
+    const int nstream = kWaves * p.num_splits;
+    const int stream = split * kWaves + wave;
+    // tiles stream, stream + nstream, ... ; none when the lengths are bad (nothing may be fetched then)
+    const int my_tiles = (!err && stream < ntile) ? (ntile - stream + nstream - 1) / nstream : 0;
+
+    const uint16_t* kbase = p.k + hk * p.g.stride_h;
+    const uint16_t* vbase = p.v + hk * p.g.stride_h;
+    const float c2 = p.scale * kLog2e;
+    unsigned char* ring = s_ring + wave * kRingBytes;
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
+    const uint32_t ring_lds = (uint32_t)(uintptr_t)(lds_byte*)ring;      // LDS byte address of the ring
+
+    // ---- tile fetch ------------------------------------------------------------------------
+    // Load instruction i of a tile moves rows RPI*i .. RPI*i+RPI-1: lane -> (row, LDS granule
+    // position); for K the lane fetches global granule position^(row % ROWG), so the tile
+    // lands XOR-swizzled.  Rows past the request's end are clamped to its last row.
+    const int lrow = lane / ROWG, lpos = lane % ROWG;
+    auto issue = [&](int j, int slot) {
+        const int tile = stream + j * nstream;
+        const uint32_t dst = ring_lds + slot * kSlotBytes;
+#pragma unroll
+        for (int i = 0; i < KLD; ++i) {
+            const int r = i * RPI + lrow;                              // row within the tile
+            const int slot_row = min(tile * kTile + r, S - 1);         // logical cache slot
+            int64_t off;
+            if (p.g.block_table) {
+                // 16-key blocks: rows 0..15 and 16..31 of the tile; uniform per load instruction
+                const int kb = __builtin_amdgcn_readfirstlane(min(tile * 2 + ((i * RPI) >> 4), (S - 1) >> 4));
+                int phys = p.g.block_table[static_cast<int64_t>(b) * p.g.max_blocks + kb];
+                phys = min(max(phys, 0), p.g.num_blocks - 1);
+                off = phys * p.g.stride_b + (slot_row & 15) * p.g.stride_t;
+            } else {
+                off = b * p.g.stride_b + static_cast<int64_t>(slot_row) * p.g.stride_t;
+            }
+            dma16(kbase + off + (lpos ^ (r & (ROWG - 1))) * 8, dst + i * 1024);
+            dma16(vbase + off + lpos * 8, dst + kTileBytes + i * 1024);
+        }
+    };
+    // the first two tiles leave before anything else is looked at
+    if (my_tiles > 0) issue(0, 0);
+    if (my_tiles > 1) issue(1, 1);
+
+    // ---- the tree: parent array -> LDS, checked once ------------------------------------------
     if (tid == 0) s_flag = 0;
     __syncthreads();
     if (tid < SPECVLM_MAX_NODES) {
@@ -136,239 +210,295 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     err |= s_flag;
     if (err) {                                  // uniform over the workgroup (and over its splits)
         if (tid == 0 && p.err_flag) atomicOr(p.err_flag, err);
+        wait_vmcnt<0>();                        // no load may still be writing this workgroup's LDS
         return;
     }
-    const int S = P + n;
-    const int nblk = (S + 15) >> 4;                                  // 16-key blocks of this request
-    const int per = (nblk + p.num_splits - 1) / p.num_splits;
-    const int blk0 = split * per;
-    const int blk1 = min(nblk, blk0 + per);                          // this workgroup: blocks [blk0, blk1)
-    const int ntile = blk1 > blk0 ? (blk1 - blk0 + 3) >> 2 : 0;      // 64-key tiles (the last may be partial)
 
-    const uint16_t* kbase = p.k + hk * p.g.stride_h;
-    const uint16_t* vbase = p.v + hk * p.g.stride_h;
-    const float c2 = p.scale * kLog2e;
-
-    // ---- tile fetch: thread -> (row, 16-byte granule); a 16-key block is one load (D=128)
-    //      or half a load (D=64) of the workgroup ------------------------------------------
-    const int lrow = tid / ROWG, lgran = tid % ROWG;
-    auto issue = [&](int tile, u32x4 (&kb)[LD], u32x4 (&vb)[LD]) {
+    // ---- Q tile -> LDS (B operand of S^T = K Q^T), XOR-swizzled like the K tiles; rows past
+    //      the node count are zero.  Keeping Q out of the registers keeps the whole kernel in
+    //      the 256 architectural VGPRs, so the accumulators never travel through AGPRs. -------
 #pragma unroll
-        for (int i = 0; i < LD; ++i) {
-            const int r = i * RPL + lrow;                             // row within the tile
-            const int blk = min(blk0 + 4 * tile + (r >> 4), blk1 - 1);  // past the range: re-read, masked later
-            const int rr = min(r & 15, S - 1 - blk * 16);             // rows past the request's end: clamp
-            int64_t off;
-            if (p.g.block_table) {
-                int phys = p.g.block_table[static_cast<int64_t>(b) * p.g.max_blocks + blk];
-                phys = min(max(phys, 0), p.g.num_blocks - 1);
-                off = phys * p.g.stride_b + rr * p.g.stride_t;
-            } else {
-                off = b * p.g.stride_b + (static_cast<int64_t>(blk) * 16 + rr) * p.g.stride_t;
-            }
-            off += lgran * 8;
-            kb[i] = *reinterpret_cast<const u32x4*>(kbase + off);
-            vb[i] = *reinterpret_cast<const u32x4*>(vbase + off);
-        }
-    };
-    auto park = [&](int stage, const u32x4 (&kb)[LD], const u32x4 (&vb)[LD]) {
-#pragma unroll
-        for (int i = 0; i < LD; ++i) {
-            const int r = i * RPL + lrow;
-            *reinterpret_cast<u32x4*>(s_k[stage] + (r * ROWG + (lgran ^ (r & (ROWG - 1)))) * 16) = kb[i];
-            *reinterpret_cast<u32x4*>(s_v[stage] + (r * ROWG + lgran) * 16) = vb[i];
-        }
-    };
-
-    u32x4 kbuf0[LD], vbuf0[LD], kbuf1[LD], vbuf1[LD];
-    if (ntile > 0) issue(0, kbuf0, vbuf0);
-    if (ntile > 1) issue(1, kbuf1, vbuf1);
-
-    // ---- this wavefront's 16 query rows: Q fragments (B operand of S^T = K Q^T): lane
-    //      (q = 16w + l16, g) holds d = 32c + 8g .. +7; rows past the node count are zero ----
-    const int qi = wave * 16 + l16;
-    const bool wave_active = wave * 16 < n;          // wavefronts without real rows only move data
-    bf16x8 qf[NC];
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
+    for (int i = 0; i < kQRows * ROWG / kThreads; ++i) {
+        const int id = tid + i * kThreads;
+        const int r = id / ROWG, u = id % ROWG;
         u32x4 w = {0u, 0u, 0u, 0u};
-        if (qi < n) w = *reinterpret_cast<const u32x4*>(p.q + b * p.q_sb + qi * p.q_sn + h * p.q_sh + (4 * c + g) * 8);
-        qf[c] = __builtin_bit_cast(bf16x8, w);
+        if (r < n) w = *reinterpret_cast<const u32x4*>(p.q + b * p.q_sb + r * p.q_sn + h * p.q_sh + u * 8);
+        *reinterpret_cast<u32x4*>(s_q + (r * ROWG + (u ^ (r & (ROWG - 1)))) * 16) = w;
     }
-    // ancestor-or-self mask of this lane's query row
-    unsigned long long anc = 0;
-    {
-        int t = qi < n ? qi : -1;
+    // ---- ancestor-or-self masks of this lane's 4 query rows ----------------------------------
+    unsigned long long anc[4];
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) {
+        unsigned long long mask = 0;
+        int t = qb * 16 + l16;
+        if (t >= n) t = -1;
         while (t != -1) {                       // parent[t] < t was checked: at most 64 steps
-            anc |= 1ull << t;
+            mask |= 1ull << t;
             t = s_par[t];
         }
+        anc[qb] = mask;
     }
 
-    float m_run = -INFINITY, l_run = 0.f;
-    f32x4 acc[NT];
+    __syncthreads();                                   // Q tile visible to all wavefronts
+    float m_run[4], mrc[4], l_run[4];    // reference max, the same times c2 (0 while -inf), running sum
+    f32x4 acc[4][NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int qb = 0; qb < 4; ++qb) {
+        m_run[qb] = -INFINITY;
+        mrc[qb] = 0.f;
+        l_run[qb] = 0.f;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[qb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 
-    auto compute = [&](int tile, int stage) {
-        const unsigned char* kt = s_k[stage];
-        const unsigned char* vt = s_v[stage];
-        // S^T = K Q^T: s[kb][i] = score of key 16kb + 4g + i (of this tile) against query qi
-        f32x4 s[4];
+    for (int j = 0; j < my_tiles; ++j) {
+        const int slot = j & 1;
+        // the tile after this one (16 load instructions... 2*KLD) may still be in flight
+        if (j + 1 < my_tiles) wait_vmcnt<2 * KLD>(); else wait_vmcnt<0>();
+        const unsigned char* kt = ring + slot * kSlotBytes;
+        const unsigned char* vt = kt + kTileBytes;
+        const int slot0 = (stream + j * nstream) * kTile;
+
+        // K fragments of the tile (A operand): lane (key = 16x + l16, g) holds d = 32c + 8g .. +7
+        bf16x8 ka[2][NC];
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
-            f32x4 a = {0.f, 0.f, 0.f, 0.f};
+        for (int x = 0; x < 2; ++x)
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
-                const int r = kb * 16 + l16;
+                const int r = x * 16 + l16;
                 const int u = 4 * c + g;
-                const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kt + (r * ROWG + (u ^ (r & (ROWG - 1)))) * 16);
-                a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[c], a, 0, 0, 0);
+                ka[x][c] = *reinterpret_cast<const bf16x8*>(kt + (r * ROWG + (u ^ (r & (ROWG - 1)))) * 16);
             }
-            s[kb] = a;
+        const bool tile_masked = slot0 + kTile > P;       // reaches past the prefix: tree region or tail
+        bf16x8 pf[4];
+#pragma unroll
+        for (int qb = 0; qb < 4; ++qb) {
+            // S^T = K Q^T: s[x][i] = score of key slot0 + 16x + 4g + i against query 16qb + l16
+            bf16x8 qf[NC];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const int r = qb * 16 + l16;
+                const int u = 4 * c + g;
+                qf[c] = *reinterpret_cast<const bf16x8*>(s_q + (r * ROWG + (u ^ (r & (ROWG - 1)))) * 16);
+            }
+            f32x4 s[2];
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+                f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int c = 0; c < NC; ++c) a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[x][c], qf[c], a, 0, 0, 0);
+                s[x] = a;
+            }
+            if (tile_masked) {
+#pragma unroll
+                for (int x = 0; x < 2; ++x)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        // branch-free on purpose: plain integer logic and one select per score
+                        const int slot_key = slot0 + x * 16 + 4 * g + i;
+                        const int rel = slot_key - P;
+                        const uint32_t in_prefix = static_cast<uint32_t>(rel) >> 31;
+                        const uint32_t is_anc = static_cast<uint32_t>(anc[qb] >> (rel & 63)) & 1u;
+                        const uint32_t in_range = static_cast<uint32_t>(slot_key - S) >> 31;
+                        const uint32_t vis = in_range & (in_prefix | is_anc);
+                        s[x][i] = vis ? s[x][i] : -INFINITY;
+                    }
+            }
+            // Online softmax with a lazily updated reference: p = exp2((s - m_ref) * c2) may exceed
+            // 1; the reference only moves when some score would exceed it by more than 2^kTau (or
+            // on the first visible key), so the common tile does no cross-lane work and never
+            // touches the accumulators.  m_ref is identical in the 4 lanes that share a query row.
+            const float lmax = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                                     fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+            const bool trig = m_run[qb] == -INFINITY ? lmax > -INFINITY : fmaf(lmax, c2, -mrc[qb]) > kTau;
+            if (__builtin_expect(__any(trig), 0)) {
+                float mx = lmax;
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run[qb], mx);
+                const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+                const float alpha = m_run[qb] == -INFINITY ? 1.f : fast_exp2((m_run[qb] - m_safe) * c2);
+                m_run[qb] = m_new;
+                mrc[qb] = m_safe * c2;
+                l_run[qb] *= alpha;                  // both are still zero while m_run was -inf
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[qb][t] *= alpha;
+            }
+            float pr[8];
+            float sum = 0.f;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) {
+                pr[jj] = fast_exp2(fmaf(s[jj >> 2][jj & 3], c2, -mrc[qb]));
+                sum += pr[jj];
+            }
+            l_run[qb] += sum;
+            u32x4 w;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) w[x] = pack_bf16x2(pr[2 * x], pr[2 * x + 1]);
+            pf[qb] = __builtin_bit_cast(bf16x8, w);
         }
-        // masks: only tiles that reach past the prefix or past this workgroup's range
-        const int tb0 = blk0 + 4 * tile;
-        const int slot0 = tb0 * 16;
-        if (slot0 + kTile > P || tb0 + 4 > blk1) {
+        // O^T += V^T P^T: contraction slot 8g + jj <-> key 16*(jj/4) + 4g + jj%4 of the tile
+        uint32_t vr[8][NT / 2];
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) {
-                const bool blk_ok = tb0 + kb < blk1;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int slot = slot0 + kb * 16 + 4 * g + i;
-                    const int rel = slot - P;
-                    const bool vis = blk_ok && slot < S && (rel < 0 || ((anc >> (rel & 63)) & 1ull));
-                    s[kb][i] = vis ? s[kb][i] : -INFINITY;
-                }
+        for (int jj = 0; jj < 8; ++jj) {
+            const int r = (jj >> 2) * 16 + 4 * g + (jj & 3);
+            if constexpr (NT == 8) {
+                const u32x4 w = *reinterpret_cast<const u32x4*>(vt + (r * ROWG + l16) * 16);
+                vr[jj][0] = w[0]; vr[jj][1] = w[1]; vr[jj][2] = w[2]; vr[jj][3] = w[3];
+            } else {
+                const u32x2 w = *reinterpret_cast<const u32x2*>(vt + r * ROWG * 16 + l16 * 8);
+                vr[jj][0] = w[0]; vr[jj][1] = w[1];
             }
         }
-        // online softmax
-        float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
-                         fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
-        mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(s[2][0], s[2][1]), fmaxf(s[2][2], s[2][3])),
-                             fmaxf(fmaxf(s[3][0], s[3][1]), fmaxf(s[3][2], s[3][3]))));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = fast_exp2((m_run - m_safe) * c2);         // exp2(-inf) = 0
-        m_run = m_new;
-        const float mc = m_safe * c2;
-        float pr[16];
-        float sum = 0.f;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            pr[j] = fast_exp2(fmaf(s[j >> 2][j & 3], c2, -mc));
-            sum += pr[j];
+        for (int t = 0; t < NT; ++t) {
+            const uint32_t sel = (t & 1) ? 0x07060302u : 0x05040100u;
+            u32x4 w;
+            w[0] = __builtin_amdgcn_perm(vr[1][t >> 1], vr[0][t >> 1], sel);
+            w[1] = __builtin_amdgcn_perm(vr[3][t >> 1], vr[2][t >> 1], sel);
+            w[2] = __builtin_amdgcn_perm(vr[5][t >> 1], vr[4][t >> 1], sel);
+            w[3] = __builtin_amdgcn_perm(vr[7][t >> 1], vr[6][t >> 1], sel);
+            const bf16x8 va = __builtin_bit_cast(bf16x8, w);
+#pragma unroll
+            for (int qb = 0; qb < 4; ++qb) acc[qb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pf[qb], acc[qb][t], 0, 0, 0);
         }
-        l_run = l_run * alpha + sum;
-        if (__any(alpha != 1.f)) {
-#pragma unroll
-            for (int t = 0; t < NT; ++t) acc[t] *= alpha;
-        }
-        // O^T += V^T P^T, 32 keys per MFMA: contraction slot 8g + j <-> key 32*half + 16*(j/4) + 4g + j%4
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            u32x4 pw;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) pw[x] = pack_bf16x2(pr[half * 8 + 2 * x], pr[half * 8 + 2 * x + 1]);
-            const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
-            uint32_t vr[8][NT / 2];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int r = half * 32 + (j >> 2) * 16 + 4 * g + (j & 3);
-                if constexpr (NT == 8) {
-                    const u32x4 w = *reinterpret_cast<const u32x4*>(vt + (r * ROWG + l16) * 16);
-                    vr[j][0] = w[0]; vr[j][1] = w[1]; vr[j][2] = w[2]; vr[j][3] = w[3];
-                } else {
-                    const u32x2 w = *reinterpret_cast<const u32x2*>(vt + r * ROWG * 16 + l16 * 8);
-                    vr[j][0] = w[0]; vr[j][1] = w[1];
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const uint32_t sel = (t & 1) ? 0x07060302u : 0x05040100u;
-                u32x4 w;
-                w[0] = __builtin_amdgcn_perm(vr[1][t >> 1], vr[0][t >> 1], sel);
-                w[1] = __builtin_amdgcn_perm(vr[3][t >> 1], vr[2][t >> 1], sel);
-                w[2] = __builtin_amdgcn_perm(vr[5][t >> 1], vr[4][t >> 1], sel);
-                w[3] = __builtin_amdgcn_perm(vr[7][t >> 1], vr[6][t >> 1], sel);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), pf, acc[t], 0, 0, 0);
-            }
-        }
-    };
+        // every LDS read of this slot has returned (its values fed the MFMAs above) before the
+        // slot is refilled: the compiler barrier keeps the reads above the refill
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (j + 2 < my_tiles) issue(j + 2, slot);
+    }
 
-    // ---- main loop: stage t%2 is consumed while tile t+1 is parked and t+2, t+3 are in flight
-    if (ntile > 0) {
-        park(0, kbuf0, vbuf0);
-        if (ntile > 2) issue(2, kbuf0, vbuf0);
+    // ---- merge the 4 streams of the workgroup --------------------------------------------------
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) {
+        l_run[qb] += __shfl_xor(l_run[qb], 16);
+        l_run[qb] += __shfl_xor(l_run[qb], 32);
+        if (g == 0) s_m[wave][qb * 16 + l16] = m_run[qb];
+    }
+    __syncthreads();                                   // also: every stream is done with its ring
+    float M[4];
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) {
+        const int qi = qb * 16 + l16;
+        M[qb] = fmaxf(fmaxf(s_m[0][qi], s_m[1][qi]), fmaxf(s_m[2][qi], s_m[3][qi]));
+        const float m_safe = M[qb] == -INFINITY ? 0.f : M[qb];
+        const float w = fast_exp2((m_run[qb] - m_safe) * c2);
+        l_run[qb] *= w;
+        if (g == 0) s_l[wave][qi] = l_run[qb];
+        // wavefront qb will own query block qb: hand it this stream's share
+        if (qb != wave) {
+            const int idx = wave < qb ? wave : wave - 1;             // 3 contributors per owner
+            f32x4* dst = reinterpret_cast<f32x4*>(s_ring) + ((qb * 3 + idx) * NT) * 64;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) dst[t * 64 + lane] = acc[qb][t] * w;
+        }
     }
     __syncthreads();
-    for (int t = 0; t < ntile; t += 2) {
-        if (t + 1 < ntile) {
-            park(1, kbuf1, vbuf1);
-            if (t + 3 < ntile) issue(t + 3, kbuf1, vbuf1);
-        }
-        if (wave_active && !(p.dbg & 4)) compute(t, 0);
-        __syncthreads();
-        if (t + 1 < ntile) {
-            if (t + 2 < ntile) {
-                park(0, kbuf0, vbuf0);
-                if (t + 4 < ntile) issue(t + 4, kbuf0, vbuf0);
-            }
-            if (wave_active && !(p.dbg & 4)) compute(t + 1, 1);
-            __syncthreads();
+    f32x4 out[NT];
+    float Mq = 0.f;
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) {
+        if (qb == wave) {
+            const float m_safe = M[qb] == -INFINITY ? 0.f : M[qb];
+            const float w = fast_exp2((m_run[qb] - m_safe) * c2);
+            const f32x4* src = reinterpret_cast<const f32x4*>(s_ring) + (qb * 3 * NT) * 64;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                out[t] = (acc[qb][t] * w + src[(0 * NT + t) * 64 + lane]) +
+                         (src[(1 * NT + t) * 64 + lane] + src[(2 * NT + t) * 64 + lane]);
+            Mq = M[qb];
         }
     }
-
-    // ---- epilogue ---------------------------------------------------------------------------
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
+    const int qi = wave * 16 + l16;
+    const float Lq = (s_l[0][qi] + s_l[1][qi]) + (s_l[2][qi] + s_l[3][qi]);
+    const bool wave_active = wave * 16 < n;            // wavefronts that own no real query row
     if (p.num_splits == 1) {
-        if (wave_active) store_rows<NT>(p, acc, m_run, l_run, b, h, qi, g, n);
+        if (wave_active) store_rows<NT>(p, out, Mq, Lq, b, h, qi, g, n);
         return;
     }
+    // ---- split partials: write-through stores, ticket, the last arrival merges ------------------
     const int64_t part0 = static_cast<int64_t>(bh) * p.num_splits;
-    if (p.dbg & 8) return;
+    // Partials are kept in bf16 (halves the bytes one compute unit must pull for the merge);
+    // the same rounding is applied to the final output anyway.  Dword i*NT/2 + t/2 of a lane
+    // packs out[t][i], out[t+1][i].
+    constexpr int PV4 = NT / 2;                        // 16-byte vectors per lane per partial
     if (wave_active) {
-        f32x4* dst = reinterpret_cast<f32x4*>(p.ws_acc) + ((part0 + split) * 4 + wave) * NT * 64;
+        u32x4* dst = reinterpret_cast<u32x4*>(p.ws_acc) + ((part0 + split) * 4 + wave) * PV4 * 64;
+        uint32_t w[4][NT / 2];
 #pragma unroll
-        for (int t = 0; t < NT; ++t) dst[t * 64 + lane] = acc[t];
-        if (g == 0) reinterpret_cast<float2*>(p.ws_ml)[(part0 + split) * kQRows + qi] = make_float2(m_run, l_run);
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int t = 0; t < NT; t += 2) w[i][t / 2] = pack_bf16x2(out[t][i], out[t + 1][i]);
+#pragma unroll
+        for (int v = 0; v < PV4; ++v) {
+            // vector v holds dwords 4v .. 4v+3 of the lane's NT*2 dwords, in (i, t/2) order
+            u32x4 x;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] = w[(4 * v + e) / (NT / 2)][(4 * v + e) % (NT / 2)];
+            store16_coherent(dst + v * 64 + lane, x);
+        }
+        if (g == 0) {
+            float* ml = p.ws_ml + ((part0 + split) * kQRows + qi) * 2;
+            __hip_atomic_store(reinterpret_cast<uint32_t*>(ml), __float_as_uint(Mq), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(reinterpret_cast<uint32_t*>(ml + 1), __float_as_uint(Lq), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
-    // the last workgroup of this (request, head) to arrive merges all partials
-    if (p.dbg & 2) return;
-    if (!(p.dbg & 1)) __threadfence();
+    wait_vmcnt<0>();                                   // the write-through stores have been acknowledged
     __syncthreads();
     if (tid == 0) {
-        const int ticket = atomicAdd(p.ws_cnt + bh, 1);
+        const int ticket = __hip_atomic_fetch_add(p.ws_cnt + bh, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int last = ticket == p.num_splits - 1;
-        if (last) p.ws_cnt[bh] = 0;                 // every other split has already drawn its ticket
+        // every other split has already drawn its ticket: leave the counter zero for the next call
+        if (last) __hip_atomic_store(p.ws_cnt + bh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_flag = last;
     }
     __syncthreads();
     if (!s_flag || !wave_active) return;
-    if (!(p.dbg & 1)) __threadfence();
-    float M = -INFINITY;
-    for (int s = 0; s < p.num_splits; ++s)
-        M = fmaxf(M, __builtin_nontemporal_load(p.ws_ml + ((part0 + s) * kQRows + qi) * 2));
-    const float m_safe = M == -INFINITY ? 0.f : M;
-    float L = 0.f;
-    f32x4 out[NT];
+    // acquire: drop whatever this compute unit / L2 may still hold of the workspace from earlier calls
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    const float2* mlp = reinterpret_cast<const float2*>(p.ws_ml) + part0 * kQRows + qi;
+    const u32x4* accp = reinterpret_cast<const u32x4*>(p.ws_acc) + (part0 * 4 + wave) * PV4 * 64 + lane;
+    // splits are taken 8 at a time with every load of a batch issued before the first use;
+    // indices past the last split are clamped and given weight zero, so there is no branch
+    const int last = p.num_splits - 1;
+    float Mall = -INFINITY;
+    for (int s0 = 0; s0 < p.num_splits; s0 += 8) {
+        float mv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mv[u] = mlp[min(s0 + u, last) * kQRows].x;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) Mall = fmaxf(Mall, mv[u]);
+    }
+    const float m_safe = Mall == -INFINITY ? 0.f : Mall;
+    float Lall = 0.f;
 #pragma unroll
     for (int t = 0; t < NT; ++t) out[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 2
-    for (int s = 0; s < p.num_splits; ++s) {
-        const float* mlp = p.ws_ml + ((part0 + s) * kQRows + qi) * 2;
-        const float ms = __builtin_nontemporal_load(mlp), ls = __builtin_nontemporal_load(mlp + 1);
-        const float w = fast_exp2((ms - m_safe) * c2);
-        L += ls * w;
-        const f32x4* src = reinterpret_cast<const f32x4*>(p.ws_acc) + ((part0 + s) * 4 + wave) * NT * 64;
+    for (int s0 = 0; s0 < p.num_splits; s0 += 8) {
+        u32x4 part[8][PV4];
+        float2 ml[8];
 #pragma unroll
-        for (int t = 0; t < NT; ++t) out[t] += __builtin_nontemporal_load(src + t * 64 + lane) * w;
+        for (int u = 0; u < 8; ++u) {
+            const int64_t se = min(s0 + u, last);
+            ml[u] = mlp[se * kQRows];
+#pragma unroll
+            for (int v = 0; v < PV4; ++v) part[u][v] = accp[(se * 4 * PV4 + v) * 64];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float w = s0 + u <= last ? fast_exp2((ml[u].x - m_safe) * c2) : 0.f;
+            Lall += ml[u].y * w;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int t = 0; t < NT; t += 2) {
+                    const int dw = i * (NT / 2) + t / 2;
+                    const uint32_t x = part[u][dw >> 2][dw & 3];
+                    out[t][i] = fmaf(__uint_as_float(x << 16), w, out[t][i]);
+                    out[t + 1][i] = fmaf(__uint_as_float(x & 0xFFFF0000u), w, out[t + 1][i]);
+                }
+        }
     }
-    store_rows<NT>(p, out, M, L, b, h, qi, g, n);
+    store_rows<NT>(p, out, Mall, Lall, b, h, qi, g, n);
 }
 
 int32_t attn_mfma_pick_splits(const specvlm_attn_desc& d) {
@@ -378,8 +508,8 @@ int32_t attn_mfma_pick_splits(const specvlm_attn_desc& d) {
     const int cap = d.paged ? d.max_blocks_per_req * SPECVLM_PAGE_SIZE : d.kv_capacity;
     // one workgroup per compute unit when a single request must fill the chip; a ragged
     // batch gets a finer grain so that the dispatcher can balance; never less than two
-    // 64-key tiles per workgroup
-    const int by_work = max(1, cap / (2 * kTile));
+    // tiles per stream
+    const int by_work = max(1, cap / (2 * kTile * kWaves));
     int want = (cus + bh - 1) / bh;
     if (d.B > 1) want *= 4;
     return max(1, min(min(want, by_work), 64));
@@ -394,7 +524,7 @@ size_t attn_mfma_workspace_bytes(const specvlm_attn_desc& d) {
     const int splits = attn_mfma_pick_splits(d);
     if (splits == 1) return 0;
     const size_t parts = static_cast<size_t>(d.B) * d.H_q * splits;
-    return counter_bytes(d) + parts * (static_cast<size_t>(kQRows) * d.D * 4 + kQRows * 8);
+    return counter_bytes(d) + parts * (static_cast<size_t>(kQRows) * d.D * 2 + kQRows * 8);
 }
 
 int32_t launch_attn_mfma(const AttnArgs& a) {
@@ -415,12 +545,11 @@ int32_t launch_attn_mfma(const AttnArgs& a) {
     p.o_sb = d.o_stride_b; p.o_sn = d.o_stride_n; p.o_sh = d.o_stride_h;
     p.prefix_len = a.prefix_len; p.num_nodes = a.num_nodes; p.parent = a.parent;
     p.err_flag = a.err_flag;
-    p.dbg = getenv("SPECVLM_DBG") ? atoi(getenv("SPECVLM_DBG")) : 0;
     const size_t parts = static_cast<size_t>(d.B) * d.H_q * p.num_splits;
     unsigned char* ws = static_cast<unsigned char*>(a.workspace);
     p.ws_cnt = reinterpret_cast<int32_t*>(ws);
     p.ws_acc = reinterpret_cast<float*>(ws + counter_bytes(d));
-    p.ws_ml = p.ws_acc + parts * kQRows * d.D;
+    p.ws_ml = p.ws_acc + parts * kQRows * d.D / 2;
     const dim3 grid(static_cast<unsigned>(parts)), block(kThreads);
     if (d.D == 128) hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, a.stream, p);
     else hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, block, 0, a.stream, p);
