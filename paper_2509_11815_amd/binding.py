@@ -46,7 +46,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     global _lib
     if _lib is not None and path is None:
         return _lib
-    path = path or _build.LIB
+    path = path or os.environ.get("SPECVLM_LIB") or _build.LIB       # SPECVLM_LIB: alternative build of the library
     if not os.path.exists(path):
         raise SpecvlmError(f"{path} is missing: build it with `python -m paper_2509_11815_amd.build` "
                            "(there is no fallback path)")

@@ -82,6 +82,14 @@ __device__ __forceinline__ void dma16(const void* gsrc, uint32_t lds_dst) {
                  : "memory");
 }
 
+// Same, 4 bytes per lane: lds_dst + 4*lane.
+__device__ __forceinline__ void dma4(const void* gsrc, uint32_t lds_dst) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :
+                 : "v"(gsrc), "s"(lds_dst)
+                 : "memory");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
@@ -145,9 +153,14 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
 
+    // Everything this kernel fetches between here and the epilogue goes through the hand-counted
+    // direct-to-LDS loads: vmcnt is one in-order counter, so a compiler-managed vector load in
+    // between would make the compiler's own wait drain every tile still in flight.  The two
+    // request scalars come through the scalar cache (constant address space, uniform index).
+    typedef const __attribute__((address_space(4))) int32_t* const_i32;
     int err = 0;
-    int n = p.num_nodes ? p.num_nodes[b] : p.N_max;
-    const int P = p.prefix_len[b];
+    int n = p.num_nodes ? ((const_i32)p.num_nodes)[b] : p.N_max;
+    const int P = ((const_i32)p.prefix_len)[b];
     if (n < 1 || n > p.N_max) err |= SPECVLM_ERR_BAD_NUM_NODES;
     n = min(max(n, 1), p.N_max);
     if (P < 0 || P + n > p.g.capacity) err |= SPECVLM_ERR_BAD_LENGTH;
@@ -160,7 +173,6 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
 
     const uint16_t* kbase = p.k + hk * p.g.stride_h;
     const uint16_t* vbase = p.v + hk * p.g.stride_h;
-    const float c2 = p.scale * kLog2e;
     unsigned char* ring = s_ring + wave * kRingBytes;
     typedef __attribute__((address_space(3))) unsigned char lds_byte;
     const uint32_t ring_lds = (uint32_t)(uintptr_t)(lds_byte*)ring;      // LDS byte address of the ring
@@ -191,55 +203,59 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
             dma16(vbase + off + lpos * 8, dst + kTileBytes + i * 1024);
         }
     };
-    // the first two tiles leave before anything else is looked at
+    typedef __attribute__((address_space(3))) int lds_int;
+    // oldest in the queue: the parent array (wavefront 0; lanes past N_max re-read its last entry)
+    // and this wavefront's quarter of the Q tile (B operand of S^T = K Q^T), XOR-swizzled like the
+    // K tiles; query rows past the node count re-read the last real row (their columns of S^T
+    // are never stored).  Keeping Q out of the registers keeps the kernel within the 256
+    // architectural VGPRs, so the accumulators never travel through AGPRs.
+    if (wave == 0)
+        dma4(p.parent + static_cast<int64_t>(b) * p.N_max + min(lane, p.N_max - 1),
+             (uint32_t)(uintptr_t)(lds_int*)s_par);
+    constexpr int QLD = 16 / RPI;                      // load instructions per 16 query rows
+#pragma unroll
+    for (int i = 0; i < QLD; ++i) {
+        const int r = wave * 16 + i * RPI + lrow;      // query row
+        const uint16_t* src = p.q + b * p.q_sb + static_cast<int64_t>(min(r, n - 1)) * p.q_sn + h * p.q_sh +
+                              (lpos ^ (r & (ROWG - 1))) * 8;
+        dma16(src, (uint32_t)(uintptr_t)(lds_byte*)s_q + (wave * 16 + i * RPI) * ROWG * 16);
+    }
+    // then the first two tiles
     if (my_tiles > 0) issue(0, 0);
     if (my_tiles > 1) issue(1, 1);
 
-    // ---- the tree: parent array -> LDS, checked once ------------------------------------------
-    if (tid == 0) s_flag = 0;
+    const float c2 = p.scale * kLog2e;
+    // parent array, Q tile and the first tile have landed (the second may still be in flight)
+    if (my_tiles > 1) wait_vmcnt<2 * KLD>(); else wait_vmcnt<0>();
     __syncthreads();
-    if (tid < SPECVLM_MAX_NODES) {
-        int par = -1;
+    // ---- the tree: checked once; ancestor-or-self masks of this lane's 4 query rows ---------------
+    {
+        bool bad = false;
         if (tid < n) {
-            par = p.parent[b * p.N_max + tid];
-            if (tid == 0 ? par != -1 : (par < 0 || par >= tid)) s_flag = SPECVLM_ERR_BAD_PARENT;
+            const int par = s_par[tid];
+            bad = tid == 0 ? par != -1 : (par < 0 || par >= tid);
         }
-        s_par[tid] = par;
+        if (__syncthreads_or(bad)) err |= SPECVLM_ERR_BAD_PARENT;
     }
-    __syncthreads();
-    err |= s_flag;
     if (err) {                                  // uniform over the workgroup (and over its splits)
         if (tid == 0 && p.err_flag) atomicOr(p.err_flag, err);
         wait_vmcnt<0>();                        // no load may still be writing this workgroup's LDS
         return;
     }
-
-    // ---- Q tile -> LDS (B operand of S^T = K Q^T), XOR-swizzled like the K tiles; rows past
-    //      the node count are zero.  Keeping Q out of the registers keeps the whole kernel in
-    //      the 256 architectural VGPRs, so the accumulators never travel through AGPRs. -------
-#pragma unroll
-    for (int i = 0; i < kQRows * ROWG / kThreads; ++i) {
-        const int id = tid + i * kThreads;
-        const int r = id / ROWG, u = id % ROWG;
-        u32x4 w = {0u, 0u, 0u, 0u};
-        if (r < n) w = *reinterpret_cast<const u32x4*>(p.q + b * p.q_sb + r * p.q_sn + h * p.q_sh + u * 8);
-        *reinterpret_cast<u32x4*>(s_q + (r * ROWG + (u ^ (r & (ROWG - 1)))) * 16) = w;
-    }
-    // ---- ancestor-or-self masks of this lane's 4 query rows ----------------------------------
     unsigned long long anc[4];
 #pragma unroll
     for (int qb = 0; qb < 4; ++qb) {
         unsigned long long mask = 0;
         int t = qb * 16 + l16;
         if (t >= n) t = -1;
-        while (t != -1) {                       // parent[t] < t was checked: at most 64 steps
+        while (t > 0) {                         // parent[t] < t was checked: at most 64 steps
             mask |= 1ull << t;
             t = s_par[t];
         }
+        if (t == 0) mask |= 1ull;
         anc[qb] = mask;
     }
 
-    __syncthreads();                                   // Q tile visible to all wavefronts
     float m_run[4], mrc[4], l_run[4];    // reference max, the same times c2 (0 while -inf), running sum
     f32x4 acc[4][NT];
 #pragma unroll
@@ -253,8 +269,6 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
 
     for (int j = 0; j < my_tiles; ++j) {
         const int slot = j & 1;
-        // the tile after this one (16 load instructions... 2*KLD) may still be in flight
-        if (j + 1 < my_tiles) wait_vmcnt<2 * KLD>(); else wait_vmcnt<0>();
         const unsigned char* kt = ring + slot * kSlotBytes;
         const unsigned char* vt = kt + kTileBytes;
         const int slot0 = (stream + j * nstream) * kTile;
@@ -366,6 +380,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         // slot is refilled: the compiler barrier keeps the reads above the refill
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         if (j + 2 < my_tiles) issue(j + 2, slot);
+        // next tile landed; the one just requested may still be in flight
+        if (j + 2 < my_tiles) wait_vmcnt<2 * KLD>(); else wait_vmcnt<0>();
     }
 
     // ---- merge the 4 streams of the workgroup --------------------------------------------------
