@@ -11,8 +11,9 @@
 //   fetch     every stream keeps a private two-slot LDS ring and fills it with direct-to-LDS
 //             loads (global_load_lds_dwordx4: no registers are tied up by bytes in flight);
 //             one load instruction moves four whole 256-byte rows, fully coalesced.  The
-//             next tile is always in flight while the current one is consumed; completion
-//             is tracked by hand with s_waitcnt vmcnt
+//             next tile is always in flight while the current one is consumed (its K half is
+//             re-requested as soon as the K fragments sit in registers); completion is
+//             tracked by hand with s_waitcnt vmcnt
 //   QK^T      S^T[32 keys x 64 q] = K . Q^T with v_mfma_f32_16x16x32_bf16; the lanes fetch
 //             K granules in XOR-swizzled order so that the operand reads (16 different rows
 //             per 16 lanes) are free of LDS bank conflicts; Q is a swizzled LDS tile too
@@ -182,26 +183,35 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     // position); for K the lane fetches global granule position^(row % ROWG), so the tile
     // lands XOR-swizzled.  Rows past the request's end are clamped to its last row.
     const int lrow = lane / ROWG, lpos = lane % ROWG;
-    auto issue = [&](int j, int slot) {
+    const int64_t lane_row_off = static_cast<int64_t>(lrow) * p.g.stride_t;
+    const int last_group = ((S - 1) / RPI) * RPI;          // first row of the last RPI-row group with a real row
+    // Element offset (from kbase / vbase) of this lane's row for load instruction i of `tile`.
+    // Everything but the last addition is wavefront-uniform (scalar ALU, scalar-cache table look-up).
+    auto row_offset = [&](int tile, int i) -> int64_t {
+        const int r0 = min(tile * kTile + i * RPI, last_group);         // uniform: first row of the group
+        int64_t base;
+        if (p.g.block_table) {
+            int phys = ((const_i32)p.g.block_table)[static_cast<int64_t>(b) * p.g.max_blocks + (r0 >> 4)];
+            phys = min(max(phys, 0), p.g.num_blocks - 1);
+            base = phys * p.g.stride_b + (r0 & 15) * p.g.stride_t;
+        } else {
+            base = b * p.g.stride_b + static_cast<int64_t>(r0) * p.g.stride_t;
+        }
+        if (r0 + RPI <= S) return base + lane_row_off;                  // uniform test: every row is real
+        return base + static_cast<int64_t>(min(lrow, S - 1 - r0)) * p.g.stride_t;
+    };
+    auto issue_k = [&](int j, int slot) {
         const int tile = stream + j * nstream;
         const uint32_t dst = ring_lds + slot * kSlotBytes;
 #pragma unroll
-        for (int i = 0; i < KLD; ++i) {
-            const int r = i * RPI + lrow;                              // row within the tile
-            const int slot_row = min(tile * kTile + r, S - 1);         // logical cache slot
-            int64_t off;
-            if (p.g.block_table) {
-                // 16-key blocks: rows 0..15 and 16..31 of the tile; uniform per load instruction
-                const int kb = __builtin_amdgcn_readfirstlane(min(tile * 2 + ((i * RPI) >> 4), (S - 1) >> 4));
-                int phys = p.g.block_table[static_cast<int64_t>(b) * p.g.max_blocks + kb];
-                phys = min(max(phys, 0), p.g.num_blocks - 1);
-                off = phys * p.g.stride_b + (slot_row & 15) * p.g.stride_t;
-            } else {
-                off = b * p.g.stride_b + static_cast<int64_t>(slot_row) * p.g.stride_t;
-            }
-            dma16(kbase + off + (lpos ^ (r & (ROWG - 1))) * 8, dst + i * 1024);
-            dma16(vbase + off + lpos * 8, dst + kTileBytes + i * 1024);
-        }
+        for (int i = 0; i < KLD; ++i)
+            dma16(kbase + row_offset(tile, i) + (lpos ^ ((i * RPI + lrow) & (ROWG - 1))) * 8, dst + i * 1024);
+    };
+    auto issue_v = [&](int j, int slot) {
+        const int tile = stream + j * nstream;
+        const uint32_t dst = ring_lds + slot * kSlotBytes + kTileBytes;
+#pragma unroll
+        for (int i = 0; i < KLD; ++i) dma16(vbase + row_offset(tile, i) + lpos * 8, dst + i * 1024);
     };
     typedef __attribute__((address_space(3))) int lds_int;
     // oldest in the queue: the parent array (wavefront 0; lanes past N_max re-read its last entry)
@@ -221,8 +231,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         dma16(src, (uint32_t)(uintptr_t)(lds_byte*)s_q + (wave * 16 + i * RPI) * ROWG * 16);
     }
     // then the first two tiles
-    if (my_tiles > 0) issue(0, 0);
-    if (my_tiles > 1) issue(1, 1);
+    if (my_tiles > 0) { issue_k(0, 0); issue_v(0, 0); }
+    if (my_tiles > 1) { issue_k(1, 1); issue_v(1, 1); }
 
     const float c2 = p.scale * kLog2e;
     // parent array, Q tile and the first tile have landed (the second may still be in flight)
@@ -283,6 +293,9 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
                 const int u = 4 * c + g;
                 ka[x][c] = *reinterpret_cast<const bf16x8*>(kt + (r * ROWG + (u ^ (r & (ROWG - 1)))) * 16);
             }
+        // the K half of this slot is free once the fragments are in registers: refill it now
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (j + 2 < my_tiles) issue_k(j + 2, slot);
         const bool tile_masked = slot0 + kTile > P;       // reaches past the prefix: tree region or tail
         bf16x8 pf[4];
 #pragma unroll
@@ -379,7 +392,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         // every LDS read of this slot has returned (its values fed the MFMAs above) before the
         // slot is refilled: the compiler barrier keeps the reads above the refill
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (j + 2 < my_tiles) issue(j + 2, slot);
+        if (j + 2 < my_tiles) issue_v(j + 2, slot);
         // next tile landed; the one just requested may still be in flight
         if (j + 2 < my_tiles) wait_vmcnt<2 * KLD>(); else wait_vmcnt<0>();
     }
@@ -477,8 +490,25 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     // splits are taken 8 at a time with every load of a batch issued before the first use;
     // indices past the last split are clamped and given weight zero, so there is no branch
     const int last = p.num_splits - 1;
+    // Splits are taken 8 at a time, every load of a batch issued before its first use; indices
+    // past the last split are clamped and given weight zero, so there is no branch.  The first
+    // batch is requested together with the reference maxima it will be weighted by.
+    u32x4 part[8][PV4];
+    float2 ml[8];
+    auto load_batch = [&](int s0) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t se = min(s0 + u, last);
+            ml[u] = mlp[se * kQRows];
+#pragma unroll
+            for (int v = 0; v < PV4; ++v) part[u][v] = accp[(se * 4 * PV4 + v) * 64];
+        }
+    };
+    load_batch(0);
     float Mall = -INFINITY;
-    for (int s0 = 0; s0 < p.num_splits; s0 += 8) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) Mall = fmaxf(Mall, ml[u].x);
+    for (int s0 = 8; s0 < p.num_splits; s0 += 8) {
         float mv[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) mv[u] = mlp[min(s0 + u, last) * kQRows].x;
@@ -490,15 +520,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) out[t] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int s0 = 0; s0 < p.num_splits; s0 += 8) {
-        u32x4 part[8][PV4];
-        float2 ml[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int64_t se = min(s0 + u, last);
-            ml[u] = mlp[se * kQRows];
-#pragma unroll
-            for (int v = 0; v < PV4; ++v) part[u][v] = accp[(se * 4 * PV4 + v) * 64];
-        }
+        if (s0 > 0) load_batch(s0);
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const float w = s0 + u <= last ? fast_exp2((ml[u].x - m_safe) * c2) : 0.f;
