@@ -27,7 +27,10 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/),
 # keyed by workload; None until measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/attn_mfma_kernel_C3.txt: 29249.6 FETCH_SIZE units x 2.000 KiB + 4841.0 WRITE_SIZE units x 1.000 KiB
+    "C3": {"read_bytes": 59903181, "write_bytes": 4957184, "bytes": 64860365},
+}
 
 
 def parse_args():
@@ -40,6 +43,8 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--attn-only", action="store_true", help="profile helper: run only the attention launches")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="profile helper: run plain device copies of a known size (scale for the HBM byte counters)")
     return ap.parse_args()
 
 
@@ -58,6 +63,15 @@ def main():
     sv.load_library()                       # fails loudly when the HIP library is missing
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        # 1 GiB read + 1 GiB written per copy kernel: the reference for FETCH_SIZE / WRITE_SIZE
+        src = torch.randint(0, 255, (1 << 30,), dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "copies": 5}))
+        return
     cfg = W.CONFIGS[args.workload]
     L, B, H, D, N = cfg.L, cfg.B, cfg.H, cfg.D, cfg.N
     P = W.prefix_lengths(cfg)
@@ -179,7 +193,7 @@ def main():
         "verify_steps_per_s": round(1e3 / ms_step, 1),
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "breakdown_ms": {"attention_all_layers": round(ms_attn, 5), "argmax_accept_compact": round(ms_tail, 5)},
-        "roofline": {"kernel": "specvlm_tree_verify_attn (split-key MFMA kernel + split merge), one layer",
+        "roofline": {"kernel": "specvlm::attn_mfma_kernel<128> (the whole specvlm_tree_verify_attn call of one layer)",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": kv_bytes_layer,
