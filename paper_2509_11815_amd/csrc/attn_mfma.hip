@@ -185,33 +185,43 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     const int lrow = lane / ROWG, lpos = lane % ROWG;
     const int64_t lane_row_off = static_cast<int64_t>(lrow) * p.g.stride_t;
     const int last_group = ((S - 1) / RPI) * RPI;          // first row of the last RPI-row group with a real row
+    // Paged cache: physical ids of the two 16-key blocks of a tile, through the scalar cache.
+    // They are looked up one tile ahead of the loads that need them, so the look-up latency
+    // never sits between a free ring slot and its refill.
+    const int last_blk = (S - 1) >> 4;
+    auto fetch_blocks = [&](int tile, int (&phys)[2]) {
+        if (!p.g.block_table) return;
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+            phys[x] = ((const_i32)p.g.block_table)[static_cast<int64_t>(b) * p.g.max_blocks + min(tile * 2 + x, last_blk)];
+    };
     // Element offset (from kbase / vbase) of this lane's row for load instruction i of `tile`.
-    // Everything but the last addition is wavefront-uniform (scalar ALU, scalar-cache table look-up).
-    auto row_offset = [&](int tile, int i) -> int64_t {
+    // Everything but the last addition is wavefront-uniform (scalar ALU).
+    auto row_offset = [&](int tile, int i, const int (&phys)[2]) -> int64_t {
         const int r0 = min(tile * kTile + i * RPI, last_group);         // uniform: first row of the group
         int64_t base;
         if (p.g.block_table) {
-            int phys = ((const_i32)p.g.block_table)[static_cast<int64_t>(b) * p.g.max_blocks + (r0 >> 4)];
-            phys = min(max(phys, 0), p.g.num_blocks - 1);
-            base = phys * p.g.stride_b + (r0 & 15) * p.g.stride_t;
+            // the group's block is block (i*RPI)/16 of the tile, or the request's last block when clamped
+            const int id = min(max(phys[(i * RPI) >> 4], 0), p.g.num_blocks - 1);
+            base = id * p.g.stride_b + (r0 & 15) * p.g.stride_t;
         } else {
             base = b * p.g.stride_b + static_cast<int64_t>(r0) * p.g.stride_t;
         }
         if (r0 + RPI <= S) return base + lane_row_off;                  // uniform test: every row is real
         return base + static_cast<int64_t>(min(lrow, S - 1 - r0)) * p.g.stride_t;
     };
-    auto issue_k = [&](int j, int slot) {
+    auto issue_k = [&](int j, int slot, const int (&phys)[2]) {
         const int tile = stream + j * nstream;
         const uint32_t dst = ring_lds + slot * kSlotBytes;
 #pragma unroll
         for (int i = 0; i < KLD; ++i)
-            dma16(kbase + row_offset(tile, i) + (lpos ^ ((i * RPI + lrow) & (ROWG - 1))) * 8, dst + i * 1024);
+            dma16(kbase + row_offset(tile, i, phys) + (lpos ^ ((i * RPI + lrow) & (ROWG - 1))) * 8, dst + i * 1024);
     };
-    auto issue_v = [&](int j, int slot) {
+    auto issue_v = [&](int j, int slot, const int (&phys)[2]) {
         const int tile = stream + j * nstream;
         const uint32_t dst = ring_lds + slot * kSlotBytes + kTileBytes;
 #pragma unroll
-        for (int i = 0; i < KLD; ++i) dma16(vbase + row_offset(tile, i) + lpos * 8, dst + i * 1024);
+        for (int i = 0; i < KLD; ++i) dma16(vbase + row_offset(tile, i, phys) + lpos * 8, dst + i * 1024);
     };
     typedef __attribute__((address_space(3))) int lds_int;
     // oldest in the queue: the parent array (wavefront 0; lanes past N_max re-read its last entry)
@@ -231,8 +241,9 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         dma16(src, (uint32_t)(uintptr_t)(lds_byte*)s_q + (wave * 16 + i * RPI) * ROWG * 16);
     }
     // then the first two tiles
-    if (my_tiles > 0) { issue_k(0, 0); issue_v(0, 0); }
-    if (my_tiles > 1) { issue_k(1, 1); issue_v(1, 1); }
+    int phys[2] = {0, 0};
+    if (my_tiles > 0) { fetch_blocks(stream, phys); issue_k(0, 0, phys); issue_v(0, 0, phys); }
+    if (my_tiles > 1) { fetch_blocks(stream + nstream, phys); issue_k(1, 1, phys); issue_v(1, 1, phys); }
 
     const float c2 = p.scale * kLog2e;
     // parent array, Q tile and the first tile have landed (the second may still be in flight)
@@ -282,6 +293,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         const unsigned char* kt = ring + slot * kSlotBytes;
         const unsigned char* vt = kt + kTileBytes;
         const int slot0 = (stream + j * nstream) * kTile;
+        if (j + 2 < my_tiles) fetch_blocks(stream + (j + 2) * nstream, phys);     // needed further down
 
         // K fragments of the tile (A operand): lane (key = 16x + l16, g) holds d = 32c + 8g .. +7
         bf16x8 ka[2][NC];
@@ -295,7 +307,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
             }
         // the K half of this slot is free once the fragments are in registers: refill it now
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (j + 2 < my_tiles) issue_k(j + 2, slot);
+        if (j + 2 < my_tiles) issue_k(j + 2, slot, phys);
         const bool tile_masked = slot0 + kTile > P;       // reaches past the prefix: tree region or tail
         bf16x8 pf[4];
 #pragma unroll
@@ -392,7 +404,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         // every LDS read of this slot has returned (its values fed the MFMAs above) before the
         // slot is refilled: the compiler barrier keeps the reads above the refill
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (j + 2 < my_tiles) issue_v(j + 2, slot);
+        if (j + 2 < my_tiles) issue_v(j + 2, slot, phys);
         // next tile landed; the one just requested may still be in flight
         if (j + 2 < my_tiles) wait_vmcnt<2 * KLD>(); else wait_vmcnt<0>();
     }
@@ -544,12 +556,11 @@ int32_t attn_mfma_pick_splits(const specvlm_attn_desc& d) {
     const int cus = 256;
     const int bh = d.B * d.H_q;
     const int cap = d.paged ? d.max_blocks_per_req * SPECVLM_PAGE_SIZE : d.kv_capacity;
-    // one workgroup per compute unit when a single request must fill the chip; a ragged
-    // batch gets a finer grain so that the dispatcher can balance; never less than two
-    // tiles per stream
-    const int by_work = max(1, cap / (2 * kTile * kWaves));
-    int want = (cus + bh - 1) / bh;
-    if (d.B > 1) want *= 4;
+    // A workgroup has a fixed cost of ~10 us (prologue, merges), so the grid is sized to ONE
+    // round of workgroups on the chip (one fits per compute unit): about cus/(B*H) splits,
+    // never so many that a stream is left without a whole tile.
+    const int by_work = max(1, cap / (kTile * kWaves));
+    const int want = max(1, (cus + bh / 2) / bh);
     return max(1, min(min(want, by_work), 64));
 }
 
