@@ -3,20 +3,24 @@
 // The step is bound by streaming K and V once from HBM (SpecVLM Sec. 3.2); all (up to 64)
 // tree queries of a head share that single pass.  Work decomposition:
 //
-//   grid      one workgroup (4 wavefronts) per (request, query head, split); the 4*splits
-//             wavefronts of a (request, head) are independent "streams": stream s owns the
-//             32-key tiles s, s + 4*splits, ... of that head and ALL 64 query rows, so a
-//             K/V byte is fetched by exactly one wavefront, and the main loop has no
-//             workgroup barrier
-//   fetch     every stream keeps a private two-slot LDS ring and fills it with direct-to-LDS
-//             loads (global_load_lds_dwordx4: no registers are tied up by bytes in flight);
-//             one load instruction moves four whole 256-byte rows, fully coalesced.  The
-//             next tile is always in flight while the current one is consumed (its K half is
-//             re-requested as soon as the K fragments sit in registers); completion is
-//             tracked by hand with s_waitcnt vmcnt
+//   grid      one workgroup (8 wavefronts, two per SIMD) per (request, query head, split).
+//             A workgroup runs 4 independent key "streams"; stream s of the 4*splits streams
+//             of a (request, head) owns the 32-key tiles s, s + 4*splits, ...  Two wavefronts
+//             share a stream: each takes 32 of the 64 query rows, so a K/V byte is fetched
+//             from HBM exactly once and read from LDS twice.  Two wavefronts per SIMD let
+//             one's matrix work overlap the other's softmax arithmetic and LDS latency
+//   fetch     every stream keeps a private two-slot LDS ring filled by direct-to-LDS loads
+//             (global_load_lds_dwordx4: no registers are tied up by bytes in flight); one load
+//             instruction moves four whole 256-byte rows, fully coalesced.  Each wavefront of
+//             the pair requests 16 of a tile's 32 rows.  Exactly one tile per stream is in
+//             flight (about 64 load instructions per compute unit, which is what the memory
+//             pipeline accepts without stalling the issuing wavefront); completion is tracked
+//             by hand with s_waitcnt vmcnt, and one workgroup barrier per tile publishes the
+//             landed halves and frees the consumed slot
 //   QK^T      S^T[32 keys x 64 q] = K . Q^T with v_mfma_f32_16x16x32_bf16; the lanes fetch
 //             K granules in XOR-swizzled order so that the operand reads (16 different rows
-//             per 16 lanes) are free of LDS bank conflicts; Q is a swizzled LDS tile too
+//             per 16 lanes) are free of LDS bank conflicts; a wavefront's Q fragments stay in
+//             registers for the whole kernel (staged once through the idle ring slot)
 //   softmax   online (running max / sum per query) in fp32 on the S^T fragments: a lane
 //             holds one query and 8 keys, so row statistics need two cross-lane steps, and
 //             exp2(S^T) packed to bf16 is already the B operand of the next MFMA
@@ -26,7 +30,8 @@
 //   masks     prefix keys need none; only tiles touching the tree region or the request's
 //             end test the per-query ancestor bit mask (select, never multiply)
 //   merge     the 4 streams of a workgroup are merged through LDS (one round, the rings
-//             are free by then); the workgroup's partial goes, as bf16, to a lane-major
+//             are free by then; 4 wavefronts each end up owning 16 query rows); the
+//             workgroup's partial goes, as bf16, to a lane-major
 //             workspace with write-through stores, and the last workgroup of a
 //             (request, head) to arrive -- found with a ticket counter -- merges the splits
 #include "common.hpp"
@@ -40,7 +45,8 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kWaves = 4;
+constexpr int kStreams = 4;         // key streams per workgroup, each with a private LDS ring
+constexpr int kWaves = 2 * kStreams; // two wavefronts per stream: 32 query rows each
 constexpr int kThreads = kWaves * 64;
 constexpr int kQRows = 64;          // padded query rows: 4 MFMA column blocks of 16
 constexpr int kTile = 32;           // keys per tile
@@ -133,12 +139,12 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     constexpr int kTileBytes = kTile * D * 2;  // one K (or V) tile
     constexpr int kSlotBytes = 2 * kTileBytes; // K tile then V tile
     constexpr int kRingBytes = kSlots * kSlotBytes;
-    static_assert(kWaves * kRingBytes >= kWaves * 3 * NT * 64 * 16, "merge scratch must fit in the rings");
+    constexpr int HALF = KLD / 2;              // load instructions per half tile (16 rows)
+    static_assert(kStreams * kRingBytes >= 4 * 3 * NT * 64 * 16, "merge scratch must fit in the rings");
 
-    __shared__ __attribute__((aligned(1024))) unsigned char s_ring[kWaves * kRingBytes];
-    __shared__ __attribute__((aligned(16))) unsigned char s_q[kQRows * D * 2];
-    __shared__ float s_m[kWaves][kQRows];
-    __shared__ float s_l[kWaves][kQRows];
+    __shared__ __attribute__((aligned(1024))) unsigned char s_ring[kStreams * kRingBytes];
+    __shared__ float s_m[kStreams][kQRows];
+    __shared__ float s_l[kStreams][kQRows];
     __shared__ int s_par[SPECVLM_MAX_NODES];
     __shared__ int s_flag;
 
@@ -152,6 +158,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     const int hk = h / p.group;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int st = wave & (kStreams - 1);      // stream of the workgroup
+    const int qh = wave >> 2;                  // query half: rows 32*qh .. 32*qh+31
     const int l16 = lane & 15, g = lane >> 4;
 
     // Everything this kernel fetches between here and the epilogue goes through the hand-counted
@@ -167,14 +175,16 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     if (P < 0 || P + n > p.g.capacity) err |= SPECVLM_ERR_BAD_LENGTH;
     const int S = P + n;
     const int ntile = (S + kTile - 1) / kTile;                       // 32-key tiles of this request
-    const int nstream = kWaves * p.num_splits;
-    const int stream = split * kWaves + wave;
+    const int nstream = kStreams * p.num_splits;
+    const int stream = split * kStreams + st;
     // tiles stream, stream + nstream, ... ; none when the lengths are bad (nothing may be fetched then)
     const int my_tiles = (!err && stream < ntile) ? (ntile - stream + nstream - 1) / nstream : 0;
+    // the workgroup's first stream has the most tiles: the (uniform) trip count of the main loop
+    const int wg_tiles = (!err && split * kStreams < ntile) ? (ntile - split * kStreams + nstream - 1) / nstream : 0;
 
     const uint16_t* kbase = p.k + hk * p.g.stride_h;
     const uint16_t* vbase = p.v + hk * p.g.stride_h;
-    unsigned char* ring = s_ring + wave * kRingBytes;
+    unsigned char* ring = s_ring + st * kRingBytes;
     typedef __attribute__((address_space(3))) unsigned char lds_byte;
     const uint32_t ring_lds = (uint32_t)(uintptr_t)(lds_byte*)ring;      // LDS byte address of the ring
 
@@ -210,46 +220,50 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         if (r0 + RPI <= S) return base + lane_row_off;                  // uniform test: every row is real
         return base + static_cast<int64_t>(min(lrow, S - 1 - r0)) * p.g.stride_t;
     };
-    auto issue_k = [&](int j, int slot, const int (&phys)[2]) {
+    // A wavefront requests the 16 rows (qh-th half) of its stream's tile, K and V: HALF loads each.
+    auto issue_half = [&](int j, int slot, const int (&phys)[2]) {
         const int tile = stream + j * nstream;
         const uint32_t dst = ring_lds + slot * kSlotBytes;
 #pragma unroll
-        for (int i = 0; i < KLD; ++i)
+        for (int ii = 0; ii < HALF; ++ii) {
+            const int i = qh * HALF + ii;
             dma16(kbase + row_offset(tile, i, phys) + (lpos ^ ((i * RPI + lrow) & (ROWG - 1))) * 8, dst + i * 1024);
-    };
-    auto issue_v = [&](int j, int slot, const int (&phys)[2]) {
-        const int tile = stream + j * nstream;
-        const uint32_t dst = ring_lds + slot * kSlotBytes + kTileBytes;
+        }
 #pragma unroll
-        for (int i = 0; i < KLD; ++i) dma16(vbase + row_offset(tile, i, phys) + lpos * 8, dst + i * 1024);
+        for (int ii = 0; ii < HALF; ++ii) {
+            const int i = qh * HALF + ii;
+            dma16(vbase + row_offset(tile, i, phys) + lpos * 8, dst + kTileBytes + i * 1024);
+        }
     };
     typedef __attribute__((address_space(3))) int lds_int;
     // oldest in the queue: the parent array (wavefront 0; lanes past N_max re-read its last entry)
-    // and this wavefront's quarter of the Q tile (B operand of S^T = K Q^T), XOR-swizzled like the
-    // K tiles; query rows past the node count re-read the last real row (their columns of S^T
-    // are never stored).  Keeping Q out of the registers keeps the kernel within the 256
-    // architectural VGPRs, so the accumulators never travel through AGPRs.
+    // and this wavefront's 32 query rows (B operand of S^T = K Q^T), XOR-swizzled like the K tiles
+    // and staged in the ring's second slot -- in exactly the two 16-row areas this wavefront itself
+    // refills later, so no other wavefront can overwrite them before they are read.  Query rows
+    // past the node count re-read the last real row (their columns of S^T are never stored).
     if (wave == 0)
         dma4(p.parent + static_cast<int64_t>(b) * p.N_max + min(lane, p.N_max - 1),
              (uint32_t)(uintptr_t)(lds_int*)s_par);
     constexpr int QLD = 16 / RPI;                      // load instructions per 16 query rows
+    const uint32_t qstage = kSlotBytes + qh * (kTileBytes / 2);          // + qb * kTileBytes
 #pragma unroll
-    for (int i = 0; i < QLD; ++i) {
-        const int r = wave * 16 + i * RPI + lrow;      // query row
-        const uint16_t* src = p.q + b * p.q_sb + static_cast<int64_t>(min(r, n - 1)) * p.q_sn + h * p.q_sh +
-                              (lpos ^ (r & (ROWG - 1))) * 8;
-        dma16(src, (uint32_t)(uintptr_t)(lds_byte*)s_q + (wave * 16 + i * RPI) * ROWG * 16);
-    }
-    // then the first two tiles
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int i = 0; i < QLD; ++i) {
+            const int r = qh * 32 + qb * 16 + i * RPI + lrow;            // query row
+            const uint16_t* src = p.q + b * p.q_sb + static_cast<int64_t>(min(r, n - 1)) * p.q_sn + h * p.q_sh +
+                                  (lpos ^ (r & (ROWG - 1))) * 8;
+            dma16(src, ring_lds + qstage + qb * kTileBytes + i * 1024);
+        }
+    // then this wavefront's half of the first tile
     int phys[2] = {0, 0};
-    if (my_tiles > 0) { fetch_blocks(stream, phys); issue_k(0, 0, phys); issue_v(0, 0, phys); }
-    if (my_tiles > 1) { fetch_blocks(stream + nstream, phys); issue_k(1, 1, phys); issue_v(1, 1, phys); }
+    if (my_tiles > 0) { fetch_blocks(stream, phys); issue_half(0, 0, phys); }
+    if (my_tiles > 1) fetch_blocks(stream + nstream, phys);
 
     const float c2 = p.scale * kLog2e;
-    // parent array, Q tile and the first tile have landed (the second may still be in flight)
-    if (my_tiles > 1) wait_vmcnt<2 * KLD>(); else wait_vmcnt<0>();
-    __syncthreads();
-    // ---- the tree: checked once; ancestor-or-self masks of this lane's 4 query rows ---------------
+    wait_vmcnt<0>();
+    __syncthreads();                            // parent array, every wavefront's Q rows and tile halves have landed
+    // ---- the tree: checked once; ancestor-or-self masks of this lane's 2 query rows ---------------
     {
         bool bad = false;
         if (tid < n) {
@@ -260,14 +274,13 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     }
     if (err) {                                  // uniform over the workgroup (and over its splits)
         if (tid == 0 && p.err_flag) atomicOr(p.err_flag, err);
-        wait_vmcnt<0>();                        // no load may still be writing this workgroup's LDS
         return;
     }
-    unsigned long long anc[4];
+    unsigned long long anc[2];
 #pragma unroll
-    for (int qb = 0; qb < 4; ++qb) {
+    for (int qb = 0; qb < 2; ++qb) {
         unsigned long long mask = 0;
-        int t = qb * 16 + l16;
+        int t = qh * 32 + qb * 16 + l16;
         if (t >= n) t = -1;
         while (t > 0) {                         // parent[t] < t was checked: at most 64 steps
             mask |= 1ull << t;
@@ -276,11 +289,22 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         if (t == 0) mask |= 1ull;
         anc[qb] = mask;
     }
-
-    float m_run[4], mrc[4], l_run[4];    // reference max, the same times c2 (0 while -inf), running sum
-    f32x4 acc[4][NT];
+    // Q fragments (B operand): lane (query 16qb + l16, g) holds d = 32c + 8g .. +7, for the whole kernel
+    bf16x8 qf[2][NC];
 #pragma unroll
-    for (int qb = 0; qb < 4; ++qb) {
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int u = 4 * c + g;
+            qf[qb][c] = *reinterpret_cast<const bf16x8*>(ring + qstage + qb * kTileBytes +
+                                                         (l16 * ROWG + (u ^ (l16 & (ROWG - 1)))) * 16);
+        }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // staged rows are in registers: the areas may be refilled
+
+    float m_run[2], mrc[2], l_run[2];    // reference max, the same times c2 (0 while -inf), running sum
+    f32x4 acc[2][NT];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
         m_run[qb] = -INFINITY;
         mrc[qb] = 0.f;
         l_run[qb] = 0.f;
@@ -288,13 +312,18 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         for (int t = 0; t < NT; ++t) acc[qb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    for (int j = 0; j < my_tiles; ++j) {
+    for (int j = 0; j < wg_tiles; ++j) {
         const int slot = j & 1;
         const unsigned char* kt = ring + slot * kSlotBytes;
         const unsigned char* vt = kt + kTileBytes;
         const int slot0 = (stream + j * nstream) * kTile;
-        if (j + 2 < my_tiles) fetch_blocks(stream + (j + 2) * nstream, phys);     // needed further down
+        // The other slot's tile was consumed by both wavefronts of the stream before the barrier
+        // that ended the previous iteration: request the next tile into it.  One tile in flight
+        // per stream keeps the memory queue short enough that issuing does not stall.
+        if (j + 1 < my_tiles) issue_half(j + 1, slot ^ 1, phys);
+        if (j + 2 < my_tiles) fetch_blocks(stream + (j + 2) * nstream, phys);     // for the next iteration
 
+        if (j < my_tiles) {
         // K fragments of the tile (A operand): lane (key = 16x + l16, g) holds d = 32c + 8g .. +7
         bf16x8 ka[2][NC];
 #pragma unroll
@@ -305,27 +334,17 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
                 const int u = 4 * c + g;
                 ka[x][c] = *reinterpret_cast<const bf16x8*>(kt + (r * ROWG + (u ^ (r & (ROWG - 1)))) * 16);
             }
-        // the K half of this slot is free once the fragments are in registers: refill it now
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (j + 2 < my_tiles) issue_k(j + 2, slot, phys);
         const bool tile_masked = slot0 + kTile > P;       // reaches past the prefix: tree region or tail
-        bf16x8 pf[4];
+        bf16x8 pf[2];
 #pragma unroll
-        for (int qb = 0; qb < 4; ++qb) {
-            // S^T = K Q^T: s[x][i] = score of key slot0 + 16x + 4g + i against query 16qb + l16
-            bf16x8 qf[NC];
-#pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                const int r = qb * 16 + l16;
-                const int u = 4 * c + g;
-                qf[c] = *reinterpret_cast<const bf16x8*>(s_q + (r * ROWG + (u ^ (r & (ROWG - 1)))) * 16);
-            }
+        for (int qb = 0; qb < 2; ++qb) {
+            // S^T = K Q^T: s[x][i] = score of key slot0 + 16x + 4g + i against query 32qh + 16qb + l16
             f32x4 s[2];
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
                 f32x4 a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int c = 0; c < NC; ++c) a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[x][c], qf[c], a, 0, 0, 0);
+                for (int c = 0; c < NC; ++c) a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[x][c], qf[qb][c], a, 0, 0, 0);
                 s[x] = a;
             }
             if (tile_masked) {
@@ -399,50 +418,53 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
             w[3] = __builtin_amdgcn_perm(vr[7][t >> 1], vr[6][t >> 1], sel);
             const bf16x8 va = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
-            for (int qb = 0; qb < 4; ++qb) acc[qb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pf[qb], acc[qb][t], 0, 0, 0);
+            for (int qb = 0; qb < 2; ++qb) acc[qb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pf[qb], acc[qb][t], 0, 0, 0);
         }
-        // every LDS read of this slot has returned (its values fed the MFMAs above) before the
-        // slot is refilled: the compiler barrier keeps the reads above the refill
+        }
+        // This wavefront's reads of the slot have returned (their values fed the MFMAs above) and
+        // its half of the next tile has landed; the barrier extends both to the whole stream.
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (j + 2 < my_tiles) issue_v(j + 2, slot, phys);
-        // next tile landed; the one just requested may still be in flight
-        if (j + 2 < my_tiles) wait_vmcnt<2 * KLD>(); else wait_vmcnt<0>();
+        wait_vmcnt<0>();
+        __syncthreads();
     }
 
     // ---- merge the 4 streams of the workgroup --------------------------------------------------
+    // Query block Q4 = 2*qh + qb (16 rows) is owned by the wavefront of stream qb in half qh; the
+    // other three streams of that half hand it their (rescaled) share through LDS.
 #pragma unroll
-    for (int qb = 0; qb < 4; ++qb) {
+    for (int qb = 0; qb < 2; ++qb) {
         l_run[qb] += __shfl_xor(l_run[qb], 16);
         l_run[qb] += __shfl_xor(l_run[qb], 32);
-        if (g == 0) s_m[wave][qb * 16 + l16] = m_run[qb];
+        if (g == 0) s_m[st][qh * 32 + qb * 16 + l16] = m_run[qb];
     }
-    __syncthreads();                                   // also: every stream is done with its ring
-    float M[4];
+    __syncthreads();                                   // (every stream was done with its ring already)
+    float M[2];
 #pragma unroll
-    for (int qb = 0; qb < 4; ++qb) {
-        const int qi = qb * 16 + l16;
+    for (int qb = 0; qb < 2; ++qb) {
+        const int qi = qh * 32 + qb * 16 + l16;
         M[qb] = fmaxf(fmaxf(s_m[0][qi], s_m[1][qi]), fmaxf(s_m[2][qi], s_m[3][qi]));
         const float m_safe = M[qb] == -INFINITY ? 0.f : M[qb];
         const float w = fast_exp2((m_run[qb] - m_safe) * c2);
         l_run[qb] *= w;
-        if (g == 0) s_l[wave][qi] = l_run[qb];
-        // wavefront qb will own query block qb: hand it this stream's share
-        if (qb != wave) {
-            const int idx = wave < qb ? wave : wave - 1;             // 3 contributors per owner
-            f32x4* dst = reinterpret_cast<f32x4*>(s_ring) + ((qb * 3 + idx) * NT) * 64;
+        if (g == 0) s_l[st][qi] = l_run[qb];
+        if (qb != st) {
+            const int idx = st < qb ? st : st - 1;                       // 3 contributors per owner
+            f32x4* dst = reinterpret_cast<f32x4*>(s_ring) + (((qh * 2 + qb) * 3 + idx) * NT) * 64;
 #pragma unroll
             for (int t = 0; t < NT; ++t) dst[t * 64 + lane] = acc[qb][t] * w;
         }
     }
     __syncthreads();
+    const bool owner = st < 2;
+    const int q4 = qh * 2 + (st & 1);                  // the query block this wavefront owns (if owner)
     f32x4 out[NT];
     float Mq = 0.f;
 #pragma unroll
-    for (int qb = 0; qb < 4; ++qb) {
-        if (qb == wave) {
+    for (int qb = 0; qb < 2; ++qb) {
+        if (qb == st) {
             const float m_safe = M[qb] == -INFINITY ? 0.f : M[qb];
             const float w = fast_exp2((m_run[qb] - m_safe) * c2);
-            const f32x4* src = reinterpret_cast<const f32x4*>(s_ring) + (qb * 3 * NT) * 64;
+            const f32x4* src = reinterpret_cast<const f32x4*>(s_ring) + (q4 * 3 * NT) * 64;
 #pragma unroll
             for (int t = 0; t < NT; ++t)
                 out[t] = (acc[qb][t] * w + src[(0 * NT + t) * 64 + lane]) +
@@ -450,9 +472,9 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
             Mq = M[qb];
         }
     }
-    const int qi = wave * 16 + l16;
+    const int qi = q4 * 16 + l16;
     const float Lq = (s_l[0][qi] + s_l[1][qi]) + (s_l[2][qi] + s_l[3][qi]);
-    const bool wave_active = wave * 16 < n;            // wavefronts that own no real query row
+    const bool wave_active = owner && q4 * 16 < n;     // wavefronts that own a real query row
     if (p.num_splits == 1) {
         if (wave_active) store_rows<NT>(p, out, Mq, Lq, b, h, qi, g, n);
         return;
@@ -464,7 +486,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     // packs out[t][i], out[t+1][i].
     constexpr int PV4 = NT / 2;                        // 16-byte vectors per lane per partial
     if (wave_active) {
-        u32x4* dst = reinterpret_cast<u32x4*>(p.ws_acc) + ((part0 + split) * 4 + wave) * PV4 * 64;
+        u32x4* dst = reinterpret_cast<u32x4*>(p.ws_acc) + ((part0 + split) * 4 + q4) * PV4 * 64;
         uint32_t w[4][NT / 2];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -498,7 +520,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     // acquire: drop whatever this compute unit / L2 may still hold of the workspace from earlier calls
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     const float2* mlp = reinterpret_cast<const float2*>(p.ws_ml) + part0 * kQRows + qi;
-    const u32x4* accp = reinterpret_cast<const u32x4*>(p.ws_acc) + (part0 * 4 + wave) * PV4 * 64 + lane;
+    const u32x4* accp = reinterpret_cast<const u32x4*>(p.ws_acc) + (part0 * 4 + q4) * PV4 * 64 + lane;
     // splits are taken 8 at a time with every load of a batch issued before the first use;
     // indices past the last split are clamped and given weight zero, so there is no branch
     const int last = p.num_splits - 1;
@@ -559,7 +581,7 @@ int32_t attn_mfma_pick_splits(const specvlm_attn_desc& d) {
     // A workgroup has a fixed cost of ~10 us (prologue, merges), so the grid is sized to ONE
     // round of workgroups on the chip (one fits per compute unit): about cus/(B*H) splits,
     // never so many that a stream is left without a whole tile.
-    const int by_work = max(1, cap / (kTile * kWaves));
+    const int by_work = max(1, cap / (kTile * kStreams));
     const int want = max(1, (cus + bh / 2) / bh);
     return max(1, min(min(want, by_work), 64));
 }
