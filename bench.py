@@ -193,7 +193,7 @@ def main():
         "verify_steps_per_s": round(1e3 / ms_step, 1),
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "breakdown_ms": {"attention_all_layers": round(ms_attn, 5), "argmax_accept_compact": round(ms_tail, 5)},
-        "roofline": {"kernel": "specvlm::attn_mfma_kernel<128> (the whole specvlm_tree_verify_attn call of one layer)",
+        "roofline": {"kernel": "specvlm::attn_mfma_kernel<128, 4, 2> (the whole specvlm_tree_verify_attn call of one layer)",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": kv_bytes_layer,

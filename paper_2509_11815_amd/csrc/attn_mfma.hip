@@ -4,19 +4,20 @@
 // tree queries of a head share that single pass.  Work decomposition:
 //
 //   grid      one workgroup (8 wavefronts, two per SIMD) per (request, query head, split).
-//             A workgroup runs 4 independent key "streams"; stream s of the 4*splits streams
-//             of a (request, head) owns the 32-key tiles s, s + 4*splits, ...  Two wavefronts
-//             share a stream: each takes 32 of the 64 query rows, so a K/V byte is fetched
-//             from HBM exactly once and read from LDS twice.  Two wavefronts per SIMD let
-//             one's matrix work overlap the other's softmax arithmetic and LDS latency
-//   fetch     every stream keeps a private two-slot LDS ring filled by direct-to-LDS loads
+//             A workgroup runs 2 independent key "streams"; stream s of the 2*splits streams
+//             of a (request, head) owns the 32-key tiles s, s + 2*splits, ...  Four wavefronts
+//             share a stream: each takes 16 of the 64 query rows, so a K/V byte is fetched
+//             from HBM exactly once and read from LDS four times.  Two wavefronts per SIMD
+//             let one's matrix work overlap the other's softmax arithmetic and LDS latency
+//   fetch     every stream keeps a private four-slot LDS ring filled by direct-to-LDS loads
 //             (global_load_lds_dwordx4: no registers are tied up by bytes in flight); one load
 //             instruction moves four whole 256-byte rows, fully coalesced.  Each wavefront of
-//             the pair requests 16 of a tile's 32 rows.  Exactly one tile per stream is in
-//             flight (about 64 load instructions per compute unit, which is what the memory
-//             pipeline accepts without stalling the issuing wavefront); completion is tracked
-//             by hand with s_waitcnt vmcnt, and one workgroup barrier per tile publishes the
-//             landed halves and frees the consumed slot
+//             a stream requests 8 of a tile's 32 rows.  Two tiles per stream are in flight
+//             ahead of the one consumed: about 64 load instructions per compute unit, which
+//             is what the memory pipeline accepts without stalling the issuing wavefront
+//             (more in flight measured slower).  Completion is tracked by hand with
+//             s_waitcnt vmcnt, and one workgroup barrier per tile publishes the landed
+//             shares and frees the consumed slot
 //   QK^T      S^T[32 keys x 64 q] = K . Q^T with v_mfma_f32_16x16x32_bf16; the lanes fetch
 //             K granules in XOR-swizzled order so that the operand reads (16 different rows
 //             per 16 lanes) are free of LDS bank conflicts; a wavefront's Q fragments stay in
@@ -29,8 +30,8 @@
 //             freely, so an operand's "8 consecutive k" are 8 rows of one column)
 //   masks     prefix keys need none; only tiles touching the tree region or the request's
 //             end test the per-query ancestor bit mask (select, never multiply)
-//   merge     the 4 streams of a workgroup are merged through LDS (one round, the rings
-//             are free by then; 4 wavefronts each end up owning 16 query rows); the
+//   merge     the streams of a workgroup are merged through LDS (one round, the rings are
+//             free by then; 4 wavefronts each end up owning 16 query rows); the
 //             workgroup's partial goes, as bf16, to a lane-major
 //             workspace with write-through stores, and the last workgroup of a
 //             (request, head) to arrive -- found with a ticket counter -- merges the splits
@@ -45,12 +46,13 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kStreams = 4;         // key streams per workgroup, each with a private LDS ring
-constexpr int kWaves = 2 * kStreams; // two wavefronts per stream: 32 query rows each
+constexpr int kWaves = 8;           // wavefronts per workgroup: two per SIMD
+constexpr int kShare = 4;           // wavefronts sharing one key stream, 64/kShare query rows each
+constexpr int kAhead = 2;           // tiles per stream kept in flight ahead of the one being consumed
+constexpr int kStreamsPerWg = kWaves / kShare;
 constexpr int kThreads = kWaves * 64;
 constexpr int kQRows = 64;          // padded query rows: 4 MFMA column blocks of 16
 constexpr int kTile = 32;           // keys per tile
-constexpr int kSlots = 2;           // ring depth per stream
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kTau = 8.0f;        // log2 of how far a probability may exceed 1 before the reference max moves
@@ -129,18 +131,29 @@ __device__ __forceinline__ void store_rows(const MfmaParams& p, const f32x4 (&ou
         p.lse[(static_cast<int64_t>(b) * p.H_q + h) * p.N_max + qi] = M * p.scale + __log2f(L) * kLn2;
 }
 
-template <int D>
+// WQ wavefronts share a stream (2: 32 query rows each, 4 streams, 2 ring slots; 4: 16 query rows
+// each, 2 streams, 4 ring slots); PD tiles per stream are kept in flight ahead of the one consumed.
+// Measured on the 2880-visual-token workload: (WQ, PD) = (4, 2) 19.5 us per layer, (4, 3) 20.0,
+// (4, 1) 20.8, (2, 1) 21.8; only (kShare, kAhead) is instantiated.
+template <int D, int WQ, int PD>
 __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
+    constexpr int kStreams = kWaves / WQ;      // key streams per workgroup, each with a private LDS ring
+    constexpr int QBW = 4 / WQ;                // 16-row query blocks per wavefront
+    constexpr int kSlots = WQ;                 // ring depth per stream (128 KB of rings in all for D = 128)
     constexpr int NC = D / 32;                 // QK^T contraction steps of 32
     constexpr int NT = D / 16;                 // PV output row blocks (O^T rows = head dim)
     constexpr int ROWG = D / 8;                // 16-byte granules per K/V row
     constexpr int RPI = 64 / ROWG;             // rows moved by one wavefront load (4 or 8)
     constexpr int KLD = kTile / RPI;           // load instructions per tile, for K and again for V
+    constexpr int KPW = KLD / WQ;              // of which this wavefront issues KPW (its 32/WQ rows)
+    constexpr int NI = 2 * KPW;                // load instructions per wavefront and tile
     constexpr int kTileBytes = kTile * D * 2;  // one K (or V) tile
     constexpr int kSlotBytes = 2 * kTileBytes; // K tile then V tile
     constexpr int kRingBytes = kSlots * kSlotBytes;
-    constexpr int HALF = KLD / 2;              // load instructions per half tile (16 rows)
-    static_assert(kStreams * kRingBytes >= 4 * 3 * NT * 64 * 16, "merge scratch must fit in the rings");
+    constexpr int QW = 16 * QBW;               // query rows per wavefront
+    static_assert(PD >= 1 && PD < kSlots, "a slot must be free for the tile being consumed");
+    static_assert(kStreams * kRingBytes >= 4 * (kStreams - 1) * NT * 64 * 16, "merge scratch must fit in the rings");
+    static_assert(QW * D * 2 == 2 * KPW * 1024, "a wavefront's Q rows fill exactly its two refill areas of one slot");
 
     __shared__ __attribute__((aligned(1024))) unsigned char s_ring[kStreams * kRingBytes];
     __shared__ float s_m[kStreams][kQRows];
@@ -158,8 +171,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     const int hk = h / p.group;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int st = wave & (kStreams - 1);      // stream of the workgroup
-    const int qh = wave >> 2;                  // query half: rows 32*qh .. 32*qh+31
+    const int st = wave % kStreams;            // stream of the workgroup
+    const int qw = wave / kStreams;            // query share: rows QW*qw .. QW*qw + QW-1
     const int l16 = lane & 15, g = lane >> 4;
 
     // Everything this kernel fetches between here and the epilogue goes through the hand-counted
@@ -220,50 +233,58 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         if (r0 + RPI <= S) return base + lane_row_off;                  // uniform test: every row is real
         return base + static_cast<int64_t>(min(lrow, S - 1 - r0)) * p.g.stride_t;
     };
-    // A wavefront requests the 16 rows (qh-th half) of its stream's tile, K and V: HALF loads each.
-    auto issue_half = [&](int j, int slot, const int (&phys)[2]) {
+    // A wavefront requests its 32/WQ rows of the stream's tile, K and V: KPW loads each, into the
+    // two areas of the slot that only this wavefront ever fills.
+    const uint32_t area = qw * KPW * 1024;                // this wavefront's area inside a K (or V) tile
+    auto issue_part = [&](int j, const int (&phys)[2]) {
         const int tile = stream + j * nstream;
-        const uint32_t dst = ring_lds + slot * kSlotBytes;
+        const uint32_t dst = ring_lds + (j % kSlots) * kSlotBytes;
 #pragma unroll
-        for (int ii = 0; ii < HALF; ++ii) {
-            const int i = qh * HALF + ii;
+        for (int ii = 0; ii < KPW; ++ii) {
+            const int i = qw * KPW + ii;
             dma16(kbase + row_offset(tile, i, phys) + (lpos ^ ((i * RPI + lrow) & (ROWG - 1))) * 8, dst + i * 1024);
         }
 #pragma unroll
-        for (int ii = 0; ii < HALF; ++ii) {
-            const int i = qh * HALF + ii;
+        for (int ii = 0; ii < KPW; ++ii) {
+            const int i = qw * KPW + ii;
             dma16(vbase + row_offset(tile, i, phys) + lpos * 8, dst + kTileBytes + i * 1024);
         }
     };
     typedef __attribute__((address_space(3))) int lds_int;
     // oldest in the queue: the parent array (wavefront 0; lanes past N_max re-read its last entry)
-    // and this wavefront's 32 query rows (B operand of S^T = K Q^T), XOR-swizzled like the K tiles
-    // and staged in the ring's second slot -- in exactly the two 16-row areas this wavefront itself
-    // refills later, so no other wavefront can overwrite them before they are read.  Query rows
-    // past the node count re-read the last real row (their columns of S^T are never stored).
+    // and this wavefront's QW query rows (B operand of S^T = K Q^T), XOR-swizzled like the K tiles
+    // and staged in the ring's last slot -- first half of the rows in this wavefront's K area,
+    // second half in its V area, the two areas only this wavefront refills later, so no other
+    // wavefront can overwrite them before they are read.  Query rows past the node count
+    // re-read the last real row (their columns of S^T are never stored).
     if (wave == 0)
         dma4(p.parent + static_cast<int64_t>(b) * p.N_max + min(lane, p.N_max - 1),
              (uint32_t)(uintptr_t)(lds_int*)s_par);
-    constexpr int QLD = 16 / RPI;                      // load instructions per 16 query rows
-    const uint32_t qstage = kSlotBytes + qh * (kTileBytes / 2);          // + qb * kTileBytes
+    constexpr uint32_t kStage = (kSlots - 1) * kSlotBytes;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int i = 0; i < QLD; ++i) {
-            const int r = qh * 32 + qb * 16 + i * RPI + lrow;            // query row
-            const uint16_t* src = p.q + b * p.q_sb + static_cast<int64_t>(min(r, n - 1)) * p.q_sn + h * p.q_sh +
-                                  (lpos ^ (r & (ROWG - 1))) * 8;
-            dma16(src, ring_lds + qstage + qb * kTileBytes + i * 1024);
-        }
-    // then this wavefront's half of the first tile
+    for (int i = 0; i < 2 * KPW; ++i) {
+        const int r = qw * QW + i * RPI + lrow;                          // query row
+        const uint16_t* src = p.q + b * p.q_sb + static_cast<int64_t>(min(r, n - 1)) * p.q_sn + h * p.q_sh +
+                              (lpos ^ (r & (ROWG - 1))) * 8;
+        dma16(src, ring_lds + kStage + (i / KPW) * kTileBytes + area + (i % KPW) * 1024);
+    }
+    // then this wavefront's share of the first PD tiles
     int phys[2] = {0, 0};
-    if (my_tiles > 0) { fetch_blocks(stream, phys); issue_half(0, 0, phys); }
-    if (my_tiles > 1) fetch_blocks(stream + nstream, phys);
+#pragma unroll
+    for (int t = 0; t < PD; ++t)
+        if (t < my_tiles) { fetch_blocks(stream + t * nstream, phys); issue_part(t, phys); }
+    if (PD < my_tiles) fetch_blocks(stream + PD * nstream, phys);
 
+    // waits until at most c tiles' worth of this wavefront's loads are outstanding (c uniform, < PD)
+    auto wait_tiles = [&](int c) {
+        if constexpr (PD >= 3) { if (c == 2) { wait_vmcnt<2 * NI>(); return; } }
+        if constexpr (PD >= 2) { if (c == 1) { wait_vmcnt<NI>(); return; } }
+        wait_vmcnt<0>();
+    };
     const float c2 = p.scale * kLog2e;
-    wait_vmcnt<0>();
-    __syncthreads();                            // parent array, every wavefront's Q rows and tile halves have landed
-    // ---- the tree: checked once; ancestor-or-self masks of this lane's 2 query rows ---------------
+    wait_tiles(max(0, min(PD, my_tiles) - 1));  // parent array, Q rows and the first tile share have landed
+    __syncthreads();
+    // ---- the tree: checked once; ancestor-or-self masks of this lane's query rows -----------------
     {
         bool bad = false;
         if (tid < n) {
@@ -274,13 +295,14 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     }
     if (err) {                                  // uniform over the workgroup (and over its splits)
         if (tid == 0 && p.err_flag) atomicOr(p.err_flag, err);
+        wait_vmcnt<0>();                        // no load may still be writing this workgroup's LDS
         return;
     }
-    unsigned long long anc[2];
+    unsigned long long anc[QBW];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QBW; ++qb) {
         unsigned long long mask = 0;
-        int t = qh * 32 + qb * 16 + l16;
+        int t = qw * QW + qb * 16 + l16;
         if (t >= n) t = -1;
         while (t > 0) {                         // parent[t] < t was checked: at most 64 steps
             mask |= 1ull << t;
@@ -290,21 +312,22 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         anc[qb] = mask;
     }
     // Q fragments (B operand): lane (query 16qb + l16, g) holds d = 32c + 8g .. +7, for the whole kernel
-    bf16x8 qf[2][NC];
+    bf16x8 qf[QBW][NC];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QBW; ++qb)
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
+            const int rr = qb * 16 + l16;                 // row within this wavefront's QW rows
             const int u = 4 * c + g;
-            qf[qb][c] = *reinterpret_cast<const bf16x8*>(ring + qstage + qb * kTileBytes +
-                                                         (l16 * ROWG + (u ^ (l16 & (ROWG - 1)))) * 16);
+            qf[qb][c] = *reinterpret_cast<const bf16x8*>(ring + kStage + (rr / (QW / 2)) * kTileBytes + area +
+                                                         ((rr % (QW / 2)) * ROWG + (u ^ (rr & (ROWG - 1)))) * 16);
         }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // staged rows are in registers: the areas may be refilled
 
-    float m_run[2], mrc[2], l_run[2];    // reference max, the same times c2 (0 while -inf), running sum
-    f32x4 acc[2][NT];
+    float m_run[QBW], mrc[QBW], l_run[QBW];    // reference max, the same times c2 (0 while -inf), running sum
+    f32x4 acc[QBW][NT];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QBW; ++qb) {
         m_run[qb] = -INFINITY;
         mrc[qb] = 0.f;
         l_run[qb] = 0.f;
@@ -313,15 +336,15 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     }
 
     for (int j = 0; j < wg_tiles; ++j) {
-        const int slot = j & 1;
-        const unsigned char* kt = ring + slot * kSlotBytes;
+        const unsigned char* kt = ring + (j % kSlots) * kSlotBytes;
         const unsigned char* vt = kt + kTileBytes;
         const int slot0 = (stream + j * nstream) * kTile;
-        // The other slot's tile was consumed by both wavefronts of the stream before the barrier
-        // that ended the previous iteration: request the next tile into it.  One tile in flight
-        // per stream keeps the memory queue short enough that issuing does not stall.
-        if (j + 1 < my_tiles) issue_half(j + 1, slot ^ 1, phys);
-        if (j + 2 < my_tiles) fetch_blocks(stream + (j + 2) * nstream, phys);     // for the next iteration
+        // The slot of tile j+PD held tile j+PD-kSlots <= j-1, consumed by every wavefront of the
+        // stream before the barrier that ended the previous iteration: request the tile into it.
+        // About 64 load instructions in flight per compute unit is what the memory pipeline
+        // takes without stalling the issuing wavefront.
+        if (j + PD < my_tiles) issue_part(j + PD, phys);
+        if (j + PD + 1 < my_tiles) fetch_blocks(stream + (j + PD + 1) * nstream, phys);     // for the next iteration
 
         if (j < my_tiles) {
         // K fragments of the tile (A operand): lane (key = 16x + l16, g) holds d = 32c + 8g .. +7
@@ -335,10 +358,10 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
                 ka[x][c] = *reinterpret_cast<const bf16x8*>(kt + (r * ROWG + (u ^ (r & (ROWG - 1)))) * 16);
             }
         const bool tile_masked = slot0 + kTile > P;       // reaches past the prefix: tree region or tail
-        bf16x8 pf[2];
+        bf16x8 pf[QBW];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            // S^T = K Q^T: s[x][i] = score of key slot0 + 16x + 4g + i against query 32qh + 16qb + l16
+        for (int qb = 0; qb < QBW; ++qb) {
+            // S^T = K Q^T: s[x][i] = score of key slot0 + 16x + 4g + i against query QW*qw + 16qb + l16
             f32x4 s[2];
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
@@ -418,63 +441,75 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
             w[3] = __builtin_amdgcn_perm(vr[7][t >> 1], vr[6][t >> 1], sel);
             const bf16x8 va = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) acc[qb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pf[qb], acc[qb][t], 0, 0, 0);
+            for (int qb = 0; qb < QBW; ++qb) acc[qb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pf[qb], acc[qb][t], 0, 0, 0);
         }
         }
         // This wavefront's reads of the slot have returned (their values fed the MFMAs above) and
-        // its half of the next tile has landed; the barrier extends both to the whole stream.
+        // its share of the next tile has landed (later tiles may still be in flight); the barrier
+        // extends both to the whole stream.
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        wait_vmcnt<0>();
+        wait_tiles(max(0, min(j + PD, my_tiles - 1) - (j + 1)));
         __syncthreads();
     }
 
-    // ---- merge the 4 streams of the workgroup --------------------------------------------------
-    // Query block Q4 = 2*qh + qb (16 rows) is owned by the wavefront of stream qb in half qh; the
-    // other three streams of that half hand it their (rescaled) share through LDS.
+    // ---- merge the streams of the workgroup ------------------------------------------------------
+    // Query block q4 = QBW*qw + qb (16 rows) is owned by the wavefront of stream q4 % kStreams in
+    // query share qw; the other streams of that share hand it their (rescaled) part through LDS.
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QBW; ++qb) {
         l_run[qb] += __shfl_xor(l_run[qb], 16);
         l_run[qb] += __shfl_xor(l_run[qb], 32);
-        if (g == 0) s_m[st][qh * 32 + qb * 16 + l16] = m_run[qb];
+        if (g == 0) s_m[st][qw * QW + qb * 16 + l16] = m_run[qb];
     }
     __syncthreads();                                   // (every stream was done with its ring already)
-    float M[2];
+    float M[QBW];
+    int own_qb = -1;                                   // uniform: the query block this wavefront owns, if any
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const int qi = qh * 32 + qb * 16 + l16;
-        M[qb] = fmaxf(fmaxf(s_m[0][qi], s_m[1][qi]), fmaxf(s_m[2][qi], s_m[3][qi]));
-        const float m_safe = M[qb] == -INFINITY ? 0.f : M[qb];
+    for (int qb = 0; qb < QBW; ++qb) {
+        const int qi = qw * QW + qb * 16 + l16;
+        const int owner_st = (qw * QBW + qb) % kStreams;
+        float mx = s_m[0][qi];
+#pragma unroll
+        for (int x = 1; x < kStreams; ++x) mx = fmaxf(mx, s_m[x][qi]);
+        M[qb] = mx;
+        const float m_safe = mx == -INFINITY ? 0.f : mx;
         const float w = fast_exp2((m_run[qb] - m_safe) * c2);
         l_run[qb] *= w;
         if (g == 0) s_l[st][qi] = l_run[qb];
-        if (qb != st) {
-            const int idx = st < qb ? st : st - 1;                       // 3 contributors per owner
-            f32x4* dst = reinterpret_cast<f32x4*>(s_ring) + (((qh * 2 + qb) * 3 + idx) * NT) * 64;
+        if (st == owner_st) {
+            own_qb = qb;
+        } else {
+            const int idx = st < owner_st ? st : st - 1;                 // kStreams-1 contributors per owner
+            f32x4* dst = reinterpret_cast<f32x4*>(s_ring) + (((qw * QBW + qb) * (kStreams - 1) + idx) * NT) * 64;
 #pragma unroll
             for (int t = 0; t < NT; ++t) dst[t * 64 + lane] = acc[qb][t] * w;
         }
     }
     __syncthreads();
-    const bool owner = st < 2;
-    const int q4 = qh * 2 + (st & 1);                  // the query block this wavefront owns (if owner)
+    const int q4 = qw * QBW + max(own_qb, 0);
     f32x4 out[NT];
     float Mq = 0.f;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        if (qb == st) {
+    for (int qb = 0; qb < QBW; ++qb) {
+        if (qb == own_qb) {
             const float m_safe = M[qb] == -INFINITY ? 0.f : M[qb];
             const float w = fast_exp2((m_run[qb] - m_safe) * c2);
-            const f32x4* src = reinterpret_cast<const f32x4*>(s_ring) + (q4 * 3 * NT) * 64;
+            const f32x4* src = reinterpret_cast<const f32x4*>(s_ring) + (q4 * (kStreams - 1) * NT) * 64;
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                out[t] = (acc[qb][t] * w + src[(0 * NT + t) * 64 + lane]) +
-                         (src[(1 * NT + t) * 64 + lane] + src[(2 * NT + t) * 64 + lane]);
+            for (int t = 0; t < NT; ++t) {
+                f32x4 o = acc[qb][t] * w;
+#pragma unroll
+                for (int x = 0; x < kStreams - 1; ++x) o += src[(x * NT + t) * 64 + lane];
+                out[t] = o;
+            }
             Mq = M[qb];
         }
     }
     const int qi = q4 * 16 + l16;
-    const float Lq = (s_l[0][qi] + s_l[1][qi]) + (s_l[2][qi] + s_l[3][qi]);
-    const bool wave_active = owner && q4 * 16 < n;     // wavefronts that own a real query row
+    float Lq = s_l[0][qi];
+#pragma unroll
+    for (int x = 1; x < kStreams; ++x) Lq += s_l[x][qi];
+    const bool wave_active = own_qb >= 0 && q4 * 16 < n;     // wavefronts that own a real query row
     if (p.num_splits == 1) {
         if (wave_active) store_rows<NT>(p, out, Mq, Lq, b, h, qi, g, n);
         return;
@@ -573,17 +608,38 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     store_rows<NT>(p, out, Mall, Lall, b, h, qi, g, n);
 }
 
+// Key-range splits per (request, head) when the caller leaves the choice to the library: the
+// count that minimises a small cost model of the kernel on 256 compute units, one workgroup
+// each.  A workgroup costs a fixed prologue + merge time plus one step per 32-key tile of its
+// longest stream; a step takes what one compute unit needs to pull its tiles through its own
+// bounded queue of outstanding loads (measured: the same with 160 or 256 units active), or
+// its share of HBM bandwidth if that is slower; workgroups beyond 256 run as further rounds.  The cache capacity stands
+// in for the request lengths, which the host does not know.
 int32_t attn_mfma_pick_splits(const specvlm_attn_desc& d) {
     if (d.num_splits > 0) return min(d.num_splits, 64);
     const int cus = 256;
     const int bh = d.B * d.H_q;
     const int cap = d.paged ? d.max_blocks_per_req * SPECVLM_PAGE_SIZE : d.kv_capacity;
-    // A workgroup has a fixed cost of ~10 us (prologue, merges), so the grid is sized to ONE
-    // round of workgroups on the chip (one fits per compute unit): about cus/(B*H) splits,
-    // never so many that a stream is left without a whole tile.
-    const int by_work = max(1, cap / (kTile * kStreams));
-    const int want = max(1, (cus + bh / 2) / bh);
-    return max(1, min(min(want, by_work), 64));
+    const int ntile = (cap + kTile - 1) / kTile;
+    const double step_bytes = static_cast<double>(kStreamsPerWg) * kTile * d.D * 2 * 2;   // K and V, bf16
+    const double bw = 6.0e6;                                     // bytes per microsecond the loop sustains
+    const double step_alone = d.D == 128 ? 1.35 : 0.9;           // microseconds per step of one compute unit by itself
+    auto wg_time = [&](int splits, int active) {
+        const int steps = (ntile + kStreamsPerWg * splits - 1) / (kStreamsPerWg * splits);
+        const double step = fmax(step_alone, step_bytes * active / bw);
+        return (splits > 1 ? 8.0 : 5.0) + steps * step;
+    };
+    const int most = max(1, min(64, ntile / kStreamsPerWg));     // never a stream without a whole tile
+    int best = 1;
+    double best_t = 1e30;
+    for (int s = 1; s <= most; ++s) {
+        const long wgs = static_cast<long>(bh) * s;
+        const long full = wgs / cus;
+        const int rest = static_cast<int>(wgs % cus);
+        const double t = full * wg_time(s, cus) + (rest ? wg_time(s, rest) : 0.0);
+        if (t < best_t * 0.999) { best_t = t; best = s; }
+    }
+    return best;
 }
 
 static size_t counter_bytes(const specvlm_attn_desc& d) {
@@ -622,8 +678,8 @@ int32_t launch_attn_mfma(const AttnArgs& a) {
     p.ws_acc = reinterpret_cast<float*>(ws + counter_bytes(d));
     p.ws_ml = p.ws_acc + parts * kQRows * d.D / 2;
     const dim3 grid(static_cast<unsigned>(parts)), block(kThreads);
-    if (d.D == 128) hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, a.stream, p);
-    else hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, block, 0, a.stream, p);
+    if (d.D == 128) hipLaunchKernelGGL((attn_mfma_kernel<128, kShare, kAhead>), grid, block, 0, a.stream, p);
+    else hipLaunchKernelGGL((attn_mfma_kernel<64, kShare, kAhead>), grid, block, 0, a.stream, p);
     return check_launch();
 }
 
