@@ -251,15 +251,20 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         }
     };
     typedef __attribute__((address_space(3))) int lds_int;
-    // oldest in the queue: the parent array (wavefront 0; lanes past N_max re-read its last entry)
-    // and this wavefront's QW query rows (B operand of S^T = K Q^T), XOR-swizzled like the K tiles
-    // and staged in the ring's last slot -- first half of the rows in this wavefront's K area,
-    // second half in its V area, the two areas only this wavefront refills later, so no other
-    // wavefront can overwrite them before they are read.  Query rows past the node count
-    // re-read the last real row (their columns of S^T are never stored).
+    // Oldest in the queue: the parent array (wavefront 0; lanes past N_max re-read its last entry),
+    // which is waited for on its own, so that the tree is checked and the ancestor masks are built
+    // while everything else is still in flight.  Then this wavefront's share of the first tile and
+    // its QW query rows (B operand of S^T = K Q^T), XOR-swizzled like the K tiles and staged in the
+    // ring's last slot -- first half of the rows in this wavefront's K area, second half in its V
+    // area, the two areas only this wavefront refills later, so no other wavefront can overwrite
+    // them before they are read (query rows past the node count re-read the last real row; their
+    // columns of S^T are never stored).  Those are what the first step needs, and together about
+    // as many load instructions as a compute unit takes at once; the tiles further ahead come after.
     if (wave == 0)
         dma4(p.parent + static_cast<int64_t>(b) * p.N_max + min(lane, p.N_max - 1),
              (uint32_t)(uintptr_t)(lds_int*)s_par);
+    int phys[2] = {0, 0};
+    if (my_tiles > 0) { fetch_blocks(stream, phys); issue_part(0, phys); }
     constexpr uint32_t kStage = (kSlots - 1) * kSlotBytes;
 #pragma unroll
     for (int i = 0; i < 2 * KPW; ++i) {
@@ -268,23 +273,25 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
                               (lpos ^ (r & (ROWG - 1))) * 8;
         dma16(src, ring_lds + kStage + (i / KPW) * kTileBytes + area + (i % KPW) * 1024);
     }
-    // then this wavefront's share of the first PD tiles
-    int phys[2] = {0, 0};
 #pragma unroll
-    for (int t = 0; t < PD; ++t)
+    for (int t = 1; t < PD; ++t)
         if (t < my_tiles) { fetch_blocks(stream + t * nstream, phys); issue_part(t, phys); }
     if (PD < my_tiles) fetch_blocks(stream + PD * nstream, phys);
 
-    // waits until at most c tiles' worth of this wavefront's loads are outstanding (c uniform, < PD)
+    // waits until at most c tiles' worth (NI instructions each; the query rows are NI too) of this
+    // wavefront's loads are outstanding (c uniform, <= PD)
     auto wait_tiles = [&](int c) {
-        if constexpr (PD >= 3) { if (c == 2) { wait_vmcnt<2 * NI>(); return; } }
-        if constexpr (PD >= 2) { if (c == 1) { wait_vmcnt<NI>(); return; } }
+        if constexpr (PD >= 3) { if (c == 3) { wait_vmcnt<3 * NI>(); return; } }
+        if constexpr (PD >= 2) { if (c == 2) { wait_vmcnt<2 * NI>(); return; } }
+        if (c == 1) { wait_vmcnt<NI>(); return; }
         wait_vmcnt<0>();
     };
     const float c2 = p.scale * kLog2e;
-    wait_tiles(max(0, min(PD, my_tiles) - 1));  // parent array, Q rows and the first tile share have landed
-    __syncthreads();
     // ---- the tree: checked once; ancestor-or-self masks of this lane's query rows -----------------
+    if (wave == 0) {
+        if (min(PD, my_tiles) == PD) wait_vmcnt<(PD + 1) * NI>(); else wait_tiles(min(PD, my_tiles) + 1);
+    }
+    __syncthreads();
     {
         bool bad = false;
         if (tid < n) {
@@ -311,6 +318,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         if (t == 0) mask |= 1ull;
         anc[qb] = mask;
     }
+    wait_tiles(max(0, min(PD, my_tiles) - 1));  // the query rows and the first tile share have landed
+    __syncthreads();                            // ... those of every wavefront
     // Q fragments (B operand): lane (query 16qb + l16, g) holds d = 32c + 8g .. +7, for the whole kernel
     bf16x8 qf[QBW][NC];
 #pragma unroll
@@ -454,61 +463,60 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
 
     // ---- merge the streams of the workgroup ------------------------------------------------------
     // Query block q4 = QBW*qw + qb (16 rows) is owned by the wavefront of stream q4 % kStreams in
-    // query share qw; the other streams of that share hand it their (rescaled) part through LDS.
-#pragma unroll
-    for (int qb = 0; qb < QBW; ++qb) {
-        l_run[qb] += __shfl_xor(l_run[qb], 16);
-        l_run[qb] += __shfl_xor(l_run[qb], 32);
-        if (g == 0) s_m[st][qw * QW + qb * 16 + l16] = m_run[qb];
-    }
-    __syncthreads();                                   // (every stream was done with its ring already)
-    float M[QBW];
+    // query share qw.  Every wavefront publishes its reference maxima and sums; the other streams
+    // of the share also hand the owner their accumulators through LDS, as they are: the owner
+    // rescales every part (its own too) to the common maximum.  One barrier.
     int own_qb = -1;                                   // uniform: the query block this wavefront owns, if any
 #pragma unroll
     for (int qb = 0; qb < QBW; ++qb) {
         const int qi = qw * QW + qb * 16 + l16;
         const int owner_st = (qw * QBW + qb) % kStreams;
-        float mx = s_m[0][qi];
-#pragma unroll
-        for (int x = 1; x < kStreams; ++x) mx = fmaxf(mx, s_m[x][qi]);
-        M[qb] = mx;
-        const float m_safe = mx == -INFINITY ? 0.f : mx;
-        const float w = fast_exp2((m_run[qb] - m_safe) * c2);
-        l_run[qb] *= w;
-        if (g == 0) s_l[st][qi] = l_run[qb];
+        l_run[qb] += __shfl_xor(l_run[qb], 16);
+        l_run[qb] += __shfl_xor(l_run[qb], 32);
+        if (g == 0) {
+            s_m[st][qi] = m_run[qb];
+            s_l[st][qi] = l_run[qb];
+        }
         if (st == owner_st) {
             own_qb = qb;
         } else {
             const int idx = st < owner_st ? st : st - 1;                 // kStreams-1 contributors per owner
             f32x4* dst = reinterpret_cast<f32x4*>(s_ring) + (((qw * QBW + qb) * (kStreams - 1) + idx) * NT) * 64;
 #pragma unroll
-            for (int t = 0; t < NT; ++t) dst[t * 64 + lane] = acc[qb][t] * w;
+            for (int t = 0; t < NT; ++t) dst[t * 64 + lane] = acc[qb][t];
         }
     }
-    __syncthreads();
+    __syncthreads();                                   // (every stream was done with its ring already)
     const int q4 = qw * QBW + max(own_qb, 0);
+    const int qi = q4 * 16 + l16;
     f32x4 out[NT];
-    float Mq = 0.f;
+    float Mq = s_m[0][qi];
 #pragma unroll
-    for (int qb = 0; qb < QBW; ++qb) {
-        if (qb == own_qb) {
-            const float m_safe = M[qb] == -INFINITY ? 0.f : M[qb];
-            const float w = fast_exp2((m_run[qb] - m_safe) * c2);
-            const f32x4* src = reinterpret_cast<const f32x4*>(s_ring) + (q4 * (kStreams - 1) * NT) * 64;
+    for (int x = 1; x < kStreams; ++x) Mq = fmaxf(Mq, s_m[x][qi]);
+    float Lq = 0.f;
+    {
+        const float m_safe = Mq == -INFINITY ? 0.f : Mq;
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                f32x4 o = acc[qb][t] * w;
+        for (int qb = 0; qb < QBW; ++qb) {
+            if (qb == own_qb) {                        // uniform
+                const float w = fast_exp2((m_run[qb] - m_safe) * c2);    // 0 for a stream that saw no visible key
+                Lq = l_run[qb] * w;
 #pragma unroll
-                for (int x = 0; x < kStreams - 1; ++x) o += src[(x * NT + t) * 64 + lane];
-                out[t] = o;
+                for (int t = 0; t < NT; ++t) out[t] = acc[qb][t] * w;
             }
-            Mq = M[qb];
+        }
+        const f32x4* src = reinterpret_cast<const f32x4*>(s_ring) + (q4 * (kStreams - 1) * NT) * 64;
+#pragma unroll
+        for (int idx = 0; idx < kStreams - 1; ++idx) {
+            const int x = idx < st ? idx : idx + 1;    // the idx-th contributor's stream
+            const float w = fast_exp2((s_m[x][qi] - m_safe) * c2);
+            Lq += s_l[x][qi] * w;
+            if (own_qb >= 0) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) out[t] += src[(idx * NT + t) * 64 + lane] * w;
+            }
         }
     }
-    const int qi = q4 * 16 + l16;
-    float Lq = s_l[0][qi];
-#pragma unroll
-    for (int x = 1; x < kStreams; ++x) Lq += s_l[x][qi];
     const bool wave_active = own_qb >= 0 && q4 * 16 < n;     // wavefronts that own a real query row
     if (p.num_splits == 1) {
         if (wave_active) store_rows<NT>(p, out, Mq, Lq, b, h, qi, g, n);
