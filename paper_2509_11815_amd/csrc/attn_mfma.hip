@@ -462,15 +462,15 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     }
 
     // ---- merge the streams of the workgroup ------------------------------------------------------
-    // Query block q4 = QBW*qw + qb (16 rows) is owned by the wavefront of stream q4 % kStreams in
-    // query share qw.  Every wavefront publishes its reference maxima and sums; the other streams
+    // Query block q4 = QBW*qw + qb (16 rows) is owned by one wavefront of query share qw, chosen
+    // so that the four owners (wavefront index kStreams*qw + stream) sit on four different SIMDs.  Every wavefront publishes its reference maxima and sums; the other streams
     // of the share also hand the owner their accumulators through LDS, as they are: the owner
     // rescales every part (its own too) to the common maximum.  One barrier.
     int own_qb = -1;                                   // uniform: the query block this wavefront owns, if any
 #pragma unroll
     for (int qb = 0; qb < QBW; ++qb) {
         const int qi = qw * QW + qb * 16 + l16;
-        const int owner_st = (qw * QBW + qb) % kStreams;
+        const int owner_st = kStreams == 2 ? ((qw * QBW + qb) >> 1) & 1 : (qw * QBW + qb) % kStreams;
         l_run[qb] += __shfl_xor(l_run[qb], 16);
         l_run[qb] += __shfl_xor(l_run[qb], 32);
         if (g == 0) {
