@@ -28,8 +28,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/),
 # keyed by workload; None until measured.
 MEASURED_TRAFFIC = {
-    # profiles/attn_mfma_kernel_C3.txt: 29249.6 FETCH_SIZE units x 2.000 KiB + 4841.0 WRITE_SIZE units x 1.000 KiB
-    "C3": {"read_bytes": 59903181, "write_bytes": 4957184, "bytes": 64860365},
+    # profiles/attn_mfma_kernel_C3.txt: 29085.6 FETCH_SIZE units x 2.000 KiB + 4841.0 WRITE_SIZE units x 1.000 KiB
+    "C3": {"read_bytes": 59567308, "write_bytes": 4957184, "bytes": 64524492},
 }
 
 
