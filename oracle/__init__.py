@@ -154,6 +154,35 @@ def tree_accept(parent, draft_tok, amax, num_nodes=None, path_cap=8):
     return accept_len, path, bonus, committed
 
 
+def tree_accept_sample(parent, draft_tok, logits, u_accept, u_bonus, *, temperature=1.0, num_nodes=None,
+                       path_cap=8):
+    """Sampling-based acceptance.  logits [B,N_max,V] (uint16 bf16 bits or float32), u_accept [B,N_max] and
+    u_bonus [B] float32 in [0,1).  Returns (accept_len, path, bonus_tok, committed_tok, margin [B] float64)."""
+    parent = _i32(parent)
+    B, N_max = parent.shape
+    draft_tok = _i32(draft_tok).reshape(B, N_max)
+    dt = _dtype_code(logits)
+    assert logits.shape[:2] == (B, N_max) and logits.strides[2] == logits.itemsize
+    V = logits.shape[2]
+    st = _estrides(logits)
+    nn = None if num_nodes is None else _i32(num_nodes)
+    ua = np.ascontiguousarray(u_accept, dtype=np.float32).reshape(B, N_max)
+    ub = np.ascontiguousarray(u_bonus, dtype=np.float32).reshape(B)
+    accept_len = np.zeros(B, dtype=np.int32)
+    path = np.zeros((B, path_cap), dtype=np.int32)
+    bonus = np.zeros(B, dtype=np.int32)
+    committed = np.zeros((B, path_cap), dtype=np.int32)
+    margin = np.zeros(B, dtype=np.float64)
+    rc = _load().oracle_tree_accept_sample(
+        ctypes.c_int(dt), ctypes.c_int(B), ctypes.c_int(N_max), ctypes.c_int(V), ctypes.c_int(path_cap),
+        _p(parent), _p(draft_tok), _p(logits), ctypes.c_int64(st[0]), ctypes.c_int64(st[1]), _p(nn),
+        ctypes.c_double(temperature), _p(ua), _p(ub),
+        _p(accept_len), _p(path), _p(bonus), _p(committed), _p(margin))
+    if rc:
+        raise ValueError(f"oracle_tree_accept_sample failed with status {rc}")
+    return accept_len, path, bonus, committed, margin
+
+
 def kv_compact(k, v, prefix_len, path, accept_len, *, block_table=None, block_size=16):
     """In-place compaction of k, v [L, ...cache dims...] (see tree_attn for the
     per-layer layouts).  Returns (new_prefix_len [B], moved_idx [B,path_cap,2])."""

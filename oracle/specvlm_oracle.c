@@ -16,14 +16,19 @@
  *                         lowest index on ties
  *   oracle_tree_accept    longest root path whose drafted tokens equal the
  *                         target's greedy tokens ("lossless" verification)
+ *   oracle_tree_accept_sample  the same walk at temperature > 0: each child is
+ *                         accepted with its residual target probability
+ *                         (speculative sampling with fixed candidates)
  *   oracle_kv_compact     move the accepted path's K/V rows to the front of
  *                         the tree region (read-all-then-write)
  *
  * Pinned by tests/test_oracle_*.py against: textbook causal attention (chain
  * tree), plain decode attention (one node), a numpy brute force with a
  * materialised mask, hand-worked fixtures under tests/golden/, the closed form
- * sigma = alpha(1-alpha^gamma)/(1-alpha) of Sec. 3.1, and exhaustive path
- * enumeration on tiny trees.
+ * sigma = alpha(1-alpha^gamma)/(1-alpha) of Sec. 3.1, exhaustive path
+ * enumeration on tiny trees, and, for the sampling walk, the exact output
+ * distribution (it must equal the target's), its zero-temperature limit (the
+ * greedy walk) and hand-computed acceptance thresholds.
  *
  * Only tests/, the smoke check and the benchmark's cpu_baseline leg may call
  * this file.  It shares no code with the HIP library.
@@ -268,6 +273,123 @@ int oracle_tree_accept(int B, int N_max, int path_cap,
         free(ok); free(depth);
     }
     return 0;
+}
+
+/*
+ * Sampling-based acceptance walk (temperature > 0).  The paper names speculative
+ * sampling as the rule that discards drafted tokens (Sec. 3.1) and evaluates
+ * temperature 1 with the same Top-K tree (Sec. 4.1) without writing the tree form
+ * out.  The reading taken here: the children of a tree node are a FIXED candidate
+ * list (top-K expansion, not draws from the draft distribution), so each candidate
+ * is a point-mass proposal and the speculative-sampling rule
+ *     accept x with probability min(1, p(x)/q(x)),  else  p <- norm(max(p - q, 0))
+ * becomes, at the current node cur with target distribution
+ *     p = softmax(logits[cur] / temperature):
+ *     for each child c of cur, in increasing node index:
+ *         x = draft_tok[c]
+ *         accept c (cur <- c, restart with c's own distribution) when
+ *             u_accept[c] < p(x) / (1 - sum of p over tokens already rejected at cur)
+ *         (a token already rejected at cur has residual probability 0: rejected again);
+ *         otherwise x joins the rejected set of cur
+ *     no child accepted: stop.
+ * The bonus token is drawn from the residual distribution at the final node
+ * (p with its rejected tokens zeroed, renormalised) by inverse CDF in vocabulary
+ * order: the lowest v with  sum_{v' <= v, v' not rejected} p(v') > u_bonus * residual mass.
+ * Each emitted token is then distributed exactly as the target's own sample.
+ *
+ * u_accept [B,N_max] and u_bonus [B] are uniform numbers in [0,1) supplied by the
+ * caller.  A child whose token is outside [0,V) is rejected.  Walking stops when
+ * the path holds path_cap nodes.  Outputs as oracle_tree_accept, plus (optional)
+ * margin[b]: the smallest distance, over every comparison taken for request b,
+ * between the uniform number and its threshold (as probabilities), so that a
+ * caller can tell decisions that a lower-precision evaluation might take
+ * differently.  Returns 0, 1 on a malformed tree, 2 on allocation failure.
+ */
+int oracle_tree_accept_sample(int dtype, int B, int N_max, int V, int path_cap,
+                              const int32_t *parent, const int32_t *draft_tok,
+                              const void *logits, int64_t stride_b, int64_t stride_n,
+                              const int32_t *num_nodes, double temperature,
+                              const float *u_accept, const float *u_bonus,
+                              int32_t *accept_len, int32_t *path, int32_t *bonus_tok,
+                              int32_t *committed_tok, double *margin)
+{
+    double *e = malloc(sizeof(double) * (size_t)V);
+    uint8_t *rejected = malloc((size_t)V);
+    if (!e || !rejected) { free(e); free(rejected); return 2; }
+    int rc = 0;
+    for (int b = 0; b < B && !rc; ++b) {
+        int n = num_nodes ? num_nodes[b] : N_max;
+        const int32_t *par = parent + (int64_t)b * N_max;
+        const int32_t *tok = draft_tok + (int64_t)b * N_max;
+        if (n < 1 || par[0] != -1) { rc = 1; break; }
+        for (int i = 1; i < n; ++i) if (par[i] < 0 || par[i] >= i) rc = 1;
+        if (rc) break;
+        int32_t *prow = path + (int64_t)b * path_cap;
+        int32_t *crow = committed_tok + (int64_t)b * path_cap;
+        for (int j = 0; j < path_cap; ++j) { prow[j] = -1; crow[j] = -1; }
+        double mg = 1.0;
+        int cur = 0, m = 0;
+        prow[0] = 0;
+        double Z = 0.0, rej_mass = 0.0;
+        for (;;) {
+            /* unnormalised target distribution at cur: e[v] = exp((l_v - max) / T) */
+            const int64_t row = (int64_t)b * stride_b + (int64_t)cur * stride_n;
+            double mx = -INFINITY;
+            for (int v = 0; v < V; ++v) { double l = elem_as_double(logits, dtype, row + v); if (l > mx) mx = l; }
+            Z = 0.0;
+            for (int v = 0; v < V; ++v) {
+                e[v] = exp((elem_as_double(logits, dtype, row + v) - mx) / temperature);
+                Z += e[v];
+                rejected[v] = 0;
+            }
+            rej_mass = 0.0;
+            int next = -1;
+            if (m + 1 < path_cap) {
+                for (int c = cur + 1; c < n && next < 0; ++c) {
+                    if (par[c] != cur) continue;
+                    const int x = tok[c];
+                    const int live = x >= 0 && x < V && !rejected[x];
+                    const double a = live ? e[x] / (Z - rej_mass) : 0.0;     /* residual probability of x */
+                    const double u = (double)u_accept[(int64_t)b * N_max + c];
+                    if (live && fabs(u - a) < mg) mg = fabs(u - a);   /* a dead token is rejected in any precision */
+                    if (u < a) {
+                        next = c;
+                    } else if (live) {
+                        rejected[x] = 1;
+                        rej_mass += e[x];
+                    }
+                }
+            }
+            if (next < 0) break;
+            cur = next;
+            prow[++m] = cur;
+        }
+        /* bonus token: inverse CDF over the residual distribution at cur */
+        const double total = Z - rej_mass;
+        const double t = (double)u_bonus[b] * total;
+        double cum = 0.0, lo = 0.0;
+        int pick = -1, last_live = -1;
+        for (int v = 0; v < V && pick < 0; ++v) {
+            if (rejected[v]) continue;
+            lo = cum;
+            cum += e[v];
+            if (e[v] > 0.0) last_live = v;
+            if (cum > t) pick = v;
+        }
+        if (pick < 0) { pick = last_live; lo = cum; }     /* rounding left t at the very end */
+        {
+            double d1 = (t - lo) / total, d2 = (cum - t) / total;
+            if (d1 < mg) mg = d1;
+            if (d2 < mg) mg = d2;
+        }
+        for (int j = 1; j <= m; ++j) crow[j - 1] = tok[prow[j]];
+        crow[m] = pick;
+        accept_len[b] = m;
+        bonus_tok[b] = pick;
+        if (margin) margin[b] = mg;
+    }
+    free(e); free(rejected);
+    return rc;
 }
 
 /*
