@@ -164,6 +164,15 @@ def main():
     ms_attn = timed(run_attn, args.steps, args.warmup)
     run_tail = make_runner(sample_and_compact)
     ms_tail = timed(run_tail, args.steps, args.warmup)
+    # not part of the step (the headline metric is greedy): the temperature-1 acceptance walk on the same trees
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(W.config_seed(cfg, 0, 9))
+    u_accept = torch.rand((B, N), device=dev, generator=gen)
+    u_bonus = torch.rand(B, device=dev, generator=gen)
+    smp_out = tuple(torch.empty_like(t) for t in acc_out)
+    run_smp = make_runner(lambda: sv.specvlm_tree_accept_sample(parent, draft_tok, logits, u_accept, u_bonus,
+                                                                temperature=1.0, err_flag=err, out=smp_out))
+    ms_smp = timed(run_smp, args.steps, args.warmup)
     assert int(err.item()) == 0, "device error flag set"
 
     kv_bytes_layer = W.kv_bytes_per_layer(cfg)
@@ -193,6 +202,7 @@ def main():
         "verify_steps_per_s": round(1e3 / ms_step, 1),
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "breakdown_ms": {"attention_all_layers": round(ms_attn, 5), "argmax_accept_compact": round(ms_tail, 5)},
+        "outside_the_step_ms": {"tree_accept_sample_T1": round(ms_smp, 5)},
         "roofline": {"kernel": "specvlm::attn_mfma_kernel<128, 4, 2> (the whole specvlm_tree_verify_attn call of one layer)",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),

@@ -51,6 +51,7 @@ typedef enum specvlm_dtype {
 #define SPECVLM_ERR_BAD_LENGTH   4   /* prefix_len[b] < 0 or prefix_len+num_nodes > capacity */
 #define SPECVLM_ERR_PATH_TOO_LONG 8  /* an accepted path would not fit in path_cap           */
 #define SPECVLM_ERR_BAD_BLOCK    16  /* block_table entry outside [0, num_blocks)            */
+#define SPECVLM_ERR_BAD_TOKEN    32  /* a drafted token outside [0, V)                       */
 
 #define SPECVLM_MAX_NODES 64
 #define SPECVLM_PAGE_SIZE 16
@@ -167,6 +168,37 @@ int32_t specvlm_tree_accept(int32_t B, int32_t N_max, int32_t path_cap,
                             const int32_t *amax_dev, const int32_t *num_nodes_dev,
                             int32_t *accept_len_dev, int32_t *path_dev, int32_t *bonus_tok_dev,
                             int32_t *committed_tok_dev, int32_t *err_flag_dev, void *stream);
+
+/*
+ * Sampling-based acceptance walk, temperature > 0 (Sec. 3.1: speculative sampling discards
+ * the incorrect drafted tokens; Sec. 4.1: temperature 1 is evaluated with the same Top-K tree,
+ * decoding stays lossless).  The children of a node are fixed candidates, i.e. point-mass
+ * proposals.  With p = softmax(logits[b,cur,:] / temperature) at the current node (cur starts
+ * at the root), the children c of cur are tried in increasing node index:
+ *     x = draft_tok[b,c];  accept c when  u_accept[b,c] < p(x) / (1 - mass rejected at cur so far),
+ *     cur <- c and continue with c's own distribution; otherwise x joins cur's rejected tokens
+ *     (a token already rejected there, or outside [0,V), is rejected outright).
+ * When no child is accepted (or the path holds path_cap nodes) the bonus token is drawn from
+ * the residual distribution at cur -- p with cur's rejected tokens removed, renormalised -- by
+ * inverse CDF in vocabulary order with u_bonus[b].  Every emitted token is distributed as the
+ * target's own sample would be.
+ *   logits_dev    device, dtype, element (b,i,v) at b*stride_b + i*stride_n + v; every visited row
+ *                 needs a finite maximum (no NaN, no +inf); -inf entries have probability 0
+ *   u_accept_dev  device fp32 [B, N_max], u_bonus_dev device fp32 [B]: uniform numbers in [0,1)
+ *                 drawn by the caller (entry c is read only if child c is tried)
+ *   outputs       as specvlm_tree_accept: accept_len, path, bonus_tok, committed_tok
+ * Arithmetic is fp32; a comparison whose two sides differ by less than fp32 rounding of the
+ * row sums may fall either way.  Stopping at path_cap with children left sets
+ * SPECVLM_ERR_PATH_TOO_LONG; a malformed parent array commits the root only and sets
+ * SPECVLM_ERR_BAD_PARENT.
+ */
+int32_t specvlm_tree_accept_sample(int32_t dtype, int32_t B, int32_t N_max, int32_t V, int32_t path_cap,
+                                   const int32_t *parent_dev, const int32_t *draft_tok_dev,
+                                   const void *logits_dev, int64_t stride_b, int64_t stride_n,
+                                   const int32_t *num_nodes_dev, float temperature,
+                                   const float *u_accept_dev, const float *u_bonus_dev,
+                                   int32_t *accept_len_dev, int32_t *path_dev, int32_t *bonus_tok_dev,
+                                   int32_t *committed_tok_dev, int32_t *err_flag_dev, void *stream);
 
 /*
  * Compaction of the accepted path's K/V rows, all layers in one call (not spelled

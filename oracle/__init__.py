@@ -157,7 +157,8 @@ def tree_accept(parent, draft_tok, amax, num_nodes=None, path_cap=8):
 def tree_accept_sample(parent, draft_tok, logits, u_accept, u_bonus, *, temperature=1.0, num_nodes=None,
                        path_cap=8):
     """Sampling-based acceptance.  logits [B,N_max,V] (uint16 bf16 bits or float32), u_accept [B,N_max] and
-    u_bonus [B] float32 in [0,1).  Returns (accept_len, path, bonus_tok, committed_tok, margin [B] float64)."""
+    u_bonus [B] float32 in [0,1).  Returns (accept_len, path, bonus_tok, committed_tok, info) where info holds
+    margin_accept [B], margin_bonus [B] (float64) and bonus_alt [B] (see the C function)."""
     parent = _i32(parent)
     B, N_max = parent.shape
     draft_tok = _i32(draft_tok).reshape(B, N_max)
@@ -172,15 +173,18 @@ def tree_accept_sample(parent, draft_tok, logits, u_accept, u_bonus, *, temperat
     path = np.zeros((B, path_cap), dtype=np.int32)
     bonus = np.zeros(B, dtype=np.int32)
     committed = np.zeros((B, path_cap), dtype=np.int32)
-    margin = np.zeros(B, dtype=np.float64)
+    margin_accept = np.zeros(B, dtype=np.float64)
+    margin_bonus = np.zeros(B, dtype=np.float64)
+    bonus_alt = np.zeros(B, dtype=np.int32)
     rc = _load().oracle_tree_accept_sample(
         ctypes.c_int(dt), ctypes.c_int(B), ctypes.c_int(N_max), ctypes.c_int(V), ctypes.c_int(path_cap),
         _p(parent), _p(draft_tok), _p(logits), ctypes.c_int64(st[0]), ctypes.c_int64(st[1]), _p(nn),
         ctypes.c_double(temperature), _p(ua), _p(ub),
-        _p(accept_len), _p(path), _p(bonus), _p(committed), _p(margin))
+        _p(accept_len), _p(path), _p(bonus), _p(committed), _p(margin_accept), _p(margin_bonus), _p(bonus_alt))
     if rc:
         raise ValueError(f"oracle_tree_accept_sample failed with status {rc}")
-    return accept_len, path, bonus, committed, margin
+    return accept_len, path, bonus, committed, dict(margin_accept=margin_accept, margin_bonus=margin_bonus,
+                                                    bonus_alt=bonus_alt)
 
 
 def kv_compact(k, v, prefix_len, path, accept_len, *, block_table=None, block_size=16):

@@ -299,11 +299,16 @@ int oracle_tree_accept(int B, int N_max, int path_cap,
  *
  * u_accept [B,N_max] and u_bonus [B] are uniform numbers in [0,1) supplied by the
  * caller.  A child whose token is outside [0,V) is rejected.  Walking stops when
- * the path holds path_cap nodes.  Outputs as oracle_tree_accept, plus (optional)
- * margin[b]: the smallest distance, over every comparison taken for request b,
- * between the uniform number and its threshold (as probabilities), so that a
- * caller can tell decisions that a lower-precision evaluation might take
- * differently.  Returns 0, 1 on a malformed tree, 2 on allocation failure.
+ * the path holds path_cap nodes.  Outputs as oracle_tree_accept, plus (each
+ * optional) what a caller needs to tell decisions that a lower-precision
+ * evaluation might take differently:
+ *   margin_accept[b]  smallest |u - threshold| over the accept comparisons taken
+ *   margin_bonus[b]   distance (as probability of the residual distribution)
+ *                     from the drawn position to the nearer edge of the bonus
+ *                     token's CDF interval
+ *   bonus_alt[b]      the token on the other side of that edge (the bonus token
+ *                     itself when there is none)
+ * Returns 0, 1 on a malformed tree, 2 on allocation failure.
  */
 int oracle_tree_accept_sample(int dtype, int B, int N_max, int V, int path_cap,
                               const int32_t *parent, const int32_t *draft_tok,
@@ -311,7 +316,8 @@ int oracle_tree_accept_sample(int dtype, int B, int N_max, int V, int path_cap,
                               const int32_t *num_nodes, double temperature,
                               const float *u_accept, const float *u_bonus,
                               int32_t *accept_len, int32_t *path, int32_t *bonus_tok,
-                              int32_t *committed_tok, double *margin)
+                              int32_t *committed_tok, double *margin_accept, double *margin_bonus,
+                              int32_t *bonus_alt)
 {
     double *e = malloc(sizeof(double) * (size_t)V);
     uint8_t *rejected = malloc((size_t)V);
@@ -368,25 +374,31 @@ int oracle_tree_accept_sample(int dtype, int B, int N_max, int V, int path_cap,
         const double total = Z - rej_mass;
         const double t = (double)u_bonus[b] * total;
         double cum = 0.0, lo = 0.0;
-        int pick = -1, last_live = -1;
+        int pick = -1, last_live = -1, prev_live = -1;
         for (int v = 0; v < V && pick < 0; ++v) {
-            if (rejected[v]) continue;
+            if (rejected[v] || !(e[v] > 0.0)) continue;
             lo = cum;
             cum += e[v];
-            if (e[v] > 0.0) last_live = v;
+            prev_live = last_live;
+            last_live = v;
             if (cum > t) pick = v;
         }
-        if (pick < 0) { pick = last_live; lo = cum; }     /* rounding left t at the very end */
+        if (pick < 0) { pick = last_live; }               /* rounding left t at the very end */
         {
-            double d1 = (t - lo) / total, d2 = (cum - t) / total;
-            if (d1 < mg) mg = d1;
-            if (d2 < mg) mg = d2;
+            int next_live = -1;
+            for (int v = pick + 1; v < V && next_live < 0; ++v)
+                if (!rejected[v] && e[v] > 0.0) next_live = v;
+            const double d_lo = (t - lo) / total, d_hi = (cum - t) / total;
+            int alt = d_lo <= d_hi ? prev_live : next_live;
+            if (alt < 0) alt = pick;
+            if (margin_bonus) margin_bonus[b] = alt == pick ? 1.0 : (d_lo <= d_hi ? d_lo : d_hi);
+            if (bonus_alt) bonus_alt[b] = alt;
         }
         for (int j = 1; j <= m; ++j) crow[j - 1] = tok[prow[j]];
         crow[m] = pick;
         accept_len[b] = m;
         bonus_tok[b] = pick;
-        if (margin) margin[b] = mg;
+        if (margin_accept) margin_accept[b] = mg;
     }
     free(e); free(rejected);
     return rc;

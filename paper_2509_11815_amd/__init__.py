@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     specvlm_kv_compact,
     specvlm_node_argmax,
     specvlm_tree_accept,
+    specvlm_tree_accept_sample,
     specvlm_tree_verify_attn,
     specvlm_tree_verify_attn_num_splits,
     specvlm_tree_verify_attn_workspace_bytes,

@@ -19,7 +19,8 @@ ERR_BITS = {1: "BAD_PARENT", 2: "BAD_NUM_NODES", 4: "BAD_LENGTH", 8: "PATH_TOO_L
 
 EXPORTS = ["specvlm_version", "specvlm_last_hip_error", "specvlm_tree_verify_attn_workspace_bytes",
            "specvlm_tree_verify_attn_num_splits",
-           "specvlm_tree_verify_attn", "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_kv_compact"]
+           "specvlm_tree_verify_attn", "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_tree_accept_sample",
+           "specvlm_kv_compact"]
 
 
 class SpecvlmError(RuntimeError):
@@ -64,6 +65,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.specvlm_node_argmax.argtypes = [i32, i32, i32, i32, vp, i64, i64, vp, vp, vp]
     L.specvlm_tree_accept.restype = i32
     L.specvlm_tree_accept.argtypes = [i32, i32, i32] + [vp] * 10
+    L.specvlm_tree_accept_sample.restype = i32
+    L.specvlm_tree_accept_sample.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, i64, i64, vp, ctypes.c_float] + [vp] * 8
     L.specvlm_kv_compact.restype = i32
     L.specvlm_kv_compact.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, vp, i64, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     _lib = L
@@ -201,6 +204,35 @@ def specvlm_tree_accept(parent, draft_tok, amax, *, num_nodes=None, path_cap=8, 
                                    _ptr(_dev_i32(num_nodes, "num_nodes")), _ptr(accept_len), _ptr(path),
                                    _ptr(bonus), _ptr(committed), _ptr(err_flag), _stream(stream))
     _check(rc, "specvlm_tree_accept")
+    return accept_len, path, bonus, committed
+
+
+def specvlm_tree_accept_sample(parent, draft_tok, logits, u_accept, u_bonus, *, temperature=1.0, num_nodes=None,
+                               path_cap=8, err_flag=None, out=None, stream=None):
+    """Sampling-based acceptance (temperature > 0).  logits [B,N_max,V]; u_accept [B,N_max] and u_bonus [B]
+    fp32 uniform numbers in [0,1).  Returns (accept_len, path, bonus_tok, committed_tok) like
+    specvlm_tree_accept."""
+    B, N_max, V = logits.shape
+    dev = logits.device
+    if logits.stride(2) != 1:
+        raise ValueError("vocab dimension must be contiguous")
+    for name, t, shape in (("u_accept", u_accept, (B, N_max)), ("u_bonus", u_bonus, (B,))):
+        if t.dtype != torch.float32 or tuple(t.shape) != shape or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous float32 tensor of shape {shape}")
+    if out is not None:
+        accept_len, path, bonus, committed = out
+        path_cap = path.shape[1]
+    else:
+        accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+        path = torch.empty((B, path_cap), dtype=torch.int32, device=dev)
+        bonus = torch.empty(B, dtype=torch.int32, device=dev)
+        committed = torch.empty((B, path_cap), dtype=torch.int32, device=dev)
+    rc = lib().specvlm_tree_accept_sample(
+        _dtype_code(logits), B, N_max, V, path_cap, _ptr(_dev_i32(parent, "parent")),
+        _ptr(_dev_i32(draft_tok, "draft_tok")), _ptr(logits), logits.stride(0), logits.stride(1),
+        _ptr(_dev_i32(num_nodes, "num_nodes")), ctypes.c_float(temperature), _ptr(u_accept), _ptr(u_bonus),
+        _ptr(accept_len), _ptr(path), _ptr(bonus), _ptr(committed), _ptr(err_flag), _stream(stream))
+    _check(rc, "specvlm_tree_accept_sample")
     return accept_len, path, bonus, committed
 
 

@@ -126,6 +126,26 @@ int32_t specvlm_tree_accept(int32_t B, int32_t N_max, int32_t path_cap, const in
                               static_cast<hipStream_t>(stream));
 }
 
+int32_t specvlm_tree_accept_sample(int32_t dtype, int32_t B, int32_t N_max, int32_t V, int32_t path_cap,
+                                   const int32_t* parent_dev, const int32_t* draft_tok_dev,
+                                   const void* logits_dev, int64_t stride_b, int64_t stride_n,
+                                   const int32_t* num_nodes_dev, float temperature,
+                                   const float* u_accept_dev, const float* u_bonus_dev,
+                                   int32_t* accept_len_dev, int32_t* path_dev, int32_t* bonus_tok_dev,
+                                   int32_t* committed_tok_dev, int32_t* err_flag_dev, void* stream) {
+    if (dtype != SPECVLM_BF16 && dtype != SPECVLM_F32) return SPECVLM_INVALID_ARG;
+    if (B < 1 || N_max < 1 || N_max > SPECVLM_MAX_NODES || V < 1 || path_cap < 1 || path_cap > SPECVLM_MAX_NODES)
+        return SPECVLM_INVALID_ARG;
+    if (!(temperature > 0.f) || stride_n < V || stride_b < 0) return SPECVLM_INVALID_ARG;
+    if (!parent_dev || !draft_tok_dev || !logits_dev || !u_accept_dev || !u_bonus_dev || !accept_len_dev ||
+        !path_dev || !bonus_tok_dev || !committed_tok_dev)
+        return SPECVLM_INVALID_ARG;
+    return launch_tree_accept_sample(dtype, B, N_max, V, path_cap, parent_dev, draft_tok_dev, logits_dev,
+                                     stride_b, stride_n, num_nodes_dev, temperature, u_accept_dev, u_bonus_dev,
+                                     accept_len_dev, path_dev, bonus_tok_dev, committed_tok_dev, err_flag_dev,
+                                     static_cast<hipStream_t>(stream));
+}
+
 int32_t specvlm_kv_compact(const specvlm_attn_desc* desc, int32_t L, void* k_base_dev, void* v_base_dev,
                            int64_t layer_stride, void* const* k_layer_ptrs_dev, void* const* v_layer_ptrs_dev,
                            const int32_t* block_table_dev, const int32_t* prefix_len_dev,

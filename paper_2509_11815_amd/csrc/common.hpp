@@ -52,6 +52,13 @@ int32_t launch_tree_accept(int32_t B, int32_t N_max, int32_t path_cap, const int
                            int32_t* accept_len, int32_t* path, int32_t* bonus_tok,
                            int32_t* committed_tok, int32_t* err_flag, hipStream_t stream);
 
+int32_t launch_tree_accept_sample(int32_t dtype, int32_t B, int32_t N_max, int32_t V, int32_t path_cap,
+                                  const int32_t* parent, const int32_t* draft_tok, const void* logits,
+                                  int64_t stride_b, int64_t stride_n, const int32_t* num_nodes,
+                                  float temperature, const float* u_accept, const float* u_bonus,
+                                  int32_t* accept_len, int32_t* path, int32_t* bonus_tok,
+                                  int32_t* committed_tok, int32_t* err_flag, hipStream_t stream);
+
 int32_t launch_kv_compact(const specvlm_attn_desc& d, int32_t L, void* k_base, void* v_base,
                           int64_t layer_stride, void* const* k_ptrs, void* const* v_ptrs,
                           const int32_t* block_table, const int32_t* prefix_len, const int32_t* path,

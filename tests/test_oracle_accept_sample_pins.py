@@ -37,7 +37,7 @@ def test_hand_worked_fixture(oracle, case):
     parent = np.array([fx["parent"]], dtype=np.int32)
     tok = np.array([fx["draft_tok"]], dtype=np.int32)
     logits = log_probs(fx["probs"]).reshape(1, 6, 3)
-    m, path, bonus, committed, margin = oracle.tree_accept_sample(
+    m, path, bonus, committed, info = oracle.tree_accept_sample(
         parent, tok, logits, [fx[case + "_u_accept"]], fx[case + "_u_bonus"], path_cap=4)
     want_path = [int(x) for x in fx[case + "_path"]]
     want_comm = [int(x) for x in fx[case + "_committed"]]
@@ -45,7 +45,7 @@ def test_hand_worked_fixture(oracle, case):
     assert path[0].tolist() == want_path + [-1] * (4 - len(want_path))
     assert committed[0].tolist() == want_comm + [-1] * (4 - len(want_comm))
     assert bonus[0] == want_comm[-1]
-    assert margin[0] > 5e-3                       # the worked numbers are not on a boundary
+    assert info["margin_accept"][0] > 5e-3 and info["margin_bonus"][0] > 5e-3   # not on a boundary
 
 
 def _tiny_tree():
