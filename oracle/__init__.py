@@ -218,3 +218,111 @@ def kv_compact(k, v, prefix_len, path, accept_len, *, block_table=None, block_si
     if rc:
         raise ValueError(f"oracle_kv_compact failed with status {rc}")
     return new_prefix, moved
+
+
+# ---- draft side: growth of the token tree (Sec. 4.1: Top-K 10, 60 tokens, depth 7) ----------------
+
+def topk_logprob(logits, K, cum=None):
+    """logits [R,V] (uint16 bf16 bits or float32), cum [R] float64 or None.
+    Returns (score [R,K] float64, token [R,K] int32, lse [R] float64)."""
+    dt = _dtype_code(logits)
+    R, V = logits.shape
+    assert logits.strides[1] == logits.itemsize
+    c = None if cum is None else np.ascontiguousarray(cum, dtype=np.float64).reshape(R)
+    score = np.zeros((R, K), dtype=np.float64)
+    token = np.zeros((R, K), dtype=np.int32)
+    lse = np.zeros(R, dtype=np.float64)
+    rc = _load().oracle_topk_logprob(
+        ctypes.c_int(dt), ctypes.c_int(R), ctypes.c_int(V), ctypes.c_int(K), _p(logits),
+        ctypes.c_int64(_estrides(logits)[0]), _p(c), _p(score), _p(token), _p(lse))
+    if rc:
+        raise ValueError(f"oracle_topk_logprob failed with status {rc}")
+    return score, token, lse
+
+
+def tree_select(score, M, num_cand=None):
+    """score [B,C] float32.  Returns (sel [B,M] int32, -1 padded; count [B]; gap [B] float64)."""
+    score = np.ascontiguousarray(score, dtype=np.float32)
+    B, C = score.shape
+    nc = None if num_cand is None else _i32(num_cand)
+    sel = np.zeros((B, M), dtype=np.int32)
+    count = np.zeros(B, dtype=np.int32)
+    gap = np.zeros(B, dtype=np.float64)
+    _load().oracle_tree_select(ctypes.c_int(B), ctypes.c_int(C), ctypes.c_int(M), _p(score), _p(nc),
+                               _p(sel), _p(count), _p(gap))
+    return sel, count, gap
+
+
+def tree_finalize(cand_score, cand_parent, cand_token, root_token, N_max, num_cand=None):
+    """Candidates [B,C] -> (parent [B,N_max], draft_tok [B,N_max], node_cand [B,N_max], num_nodes [B],
+    gap [B] float64)."""
+    cand_score = np.ascontiguousarray(cand_score, dtype=np.float32)
+    B, C = cand_score.shape
+    cp = _i32(cand_parent).reshape(B, C)
+    ct = _i32(cand_token).reshape(B, C)
+    rt = _i32(root_token).reshape(B)
+    nc = None if num_cand is None else _i32(num_cand)
+    parent = np.zeros((B, N_max), dtype=np.int32)
+    tok = np.zeros((B, N_max), dtype=np.int32)
+    node_cand = np.zeros((B, N_max), dtype=np.int32)
+    num_nodes = np.zeros(B, dtype=np.int32)
+    gap = np.zeros(B, dtype=np.float64)
+    rc = _load().oracle_tree_finalize(
+        ctypes.c_int(B), ctypes.c_int(C), ctypes.c_int(N_max), _p(cand_score), _p(cp), _p(ct), _p(nc), _p(rt),
+        _p(parent), _p(tok), _p(node_cand), _p(num_nodes), _p(gap))
+    if rc:
+        raise ValueError(f"oracle_tree_finalize failed with status {rc}")
+    return parent, tok, node_cand, num_nodes, gap
+
+
+def grow_tree(level_logits, root_token, *, K=10, width=10, N_max=60):
+    """Whole growth of one batch of draft trees from the draft model's logits.
+
+    level_logits[0] is [B,1,V] (the root's next-token logits); level_logits[d], d >= 1, is
+    [B,rows_d,V] with rows_d = min(width, candidates made by level d-1): row r belongs to the r-th
+    node chosen for expansion at depth d (chosen nodes are listed in increasing candidate index).
+    Level d expands its nodes by their Top-K tokens; a candidate's value is the sum of the
+    log-probabilities on its root path, kept as float32 (the stored number every later choice is
+    taken on); the `width` most valuable new candidates are expanded next; in the end the
+    N_max - 1 most valuable candidates of all levels form the tree.
+
+    Returns a dict: cand_score/cand_parent/cand_token [B,C], level_sel (list of [B,rows_d] global
+    candidate indices), level_gap (list of [B]), and the outputs of tree_finalize.
+    """
+    depth = len(level_logits)
+    B = level_logits[0].shape[0]
+    V = level_logits[0].shape[2]
+    C = sum(lg.shape[1] * K for lg in level_logits)
+    cand_score = np.zeros((B, C), dtype=np.float32)
+    cand_parent = np.full((B, C), -1, dtype=np.int32)
+    cand_token = np.zeros((B, C), dtype=np.int32)
+    level_sel, level_gap = [], []
+    base, count = 0, 0                       # candidate range created by the previous level
+    for d in range(depth):
+        lg = level_logits[d]
+        rows = lg.shape[1]
+        if d == 0:
+            assert rows == 1
+            cum = np.zeros((B, 1), dtype=np.float64)
+            par = np.full((B, 1), -1, dtype=np.int32)
+            new_base = 0
+        else:
+            assert rows == min(width, count)
+            sel, cnt, gap = tree_select(cand_score[:, base:base + count], rows)
+            assert np.all(cnt == rows)
+            sel = sel + base
+            level_sel.append(sel)
+            level_gap.append(gap)
+            cum = np.take_along_axis(cand_score, sel, axis=1).astype(np.float64)
+            par = sel
+            new_base = base + count
+        sc, tk, _ = topk_logprob(np.ascontiguousarray(lg).reshape(B * rows, V), K, cum.reshape(-1))
+        n_new = rows * K
+        cand_score[:, new_base:new_base + n_new] = sc.reshape(B, n_new).astype(np.float32)
+        cand_token[:, new_base:new_base + n_new] = tk.reshape(B, n_new)
+        cand_parent[:, new_base:new_base + n_new] = np.repeat(par, K, axis=1)
+        base, count = new_base, n_new
+    parent, tok, node_cand, num_nodes, gap = tree_finalize(cand_score, cand_parent, cand_token, root_token, N_max)
+    return dict(cand_score=cand_score, cand_parent=cand_parent, cand_token=cand_token, level_sel=level_sel,
+                level_gap=level_gap, parent=parent, draft_tok=tok, node_cand=node_cand, num_nodes=num_nodes,
+                final_gap=gap)

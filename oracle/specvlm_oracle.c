@@ -21,6 +21,9 @@
  *                         (speculative sampling with fixed candidates)
  *   oracle_kv_compact     move the accepted path's K/V rows to the front of
  *                         the tree region (read-all-then-write)
+ *   oracle_topk_logprob, oracle_tree_select, oracle_tree_finalize
+ *                         the draft side: Top-K expansion of a level, choice of
+ *                         the next level's nodes, and the final tree
  *
  * Pinned by tests/test_oracle_*.py against: textbook causal attention (chain
  * tree), plain decode attention (one node), a numpy brute force with a
@@ -28,7 +31,11 @@
  * sigma = alpha(1-alpha^gamma)/(1-alpha) of Sec. 3.1, exhaustive path
  * enumeration on tiny trees, and, for the sampling walk, the exact output
  * distribution (it must equal the target's), its zero-temperature limit (the
- * greedy walk) and hand-computed acceptance thresholds.
+ * greedy walk) and hand-computed acceptance thresholds; for the draft-side
+ * growth, a hand-worked fixture, scipy's log_softmax / logsumexp and numpy's
+ * stable sort, closed forms (uniform logits, probabilities summing to one) and
+ * enumeration of all token sequences (an exhaustively expanded tree must hold
+ * exactly the most probable sequences).
  *
  * Only tests/, the smoke check and the benchmark's cpu_baseline leg may call
  * this file.  It shares no code with the HIP library.
@@ -401,6 +408,142 @@ int oracle_tree_accept_sample(int dtype, int B, int N_max, int V, int path_cap,
         if (margin_accept) margin_accept[b] = mg;
     }
     free(e); free(rejected);
+    return rc;
+}
+
+/*
+ * ---- draft-side tree growth (Sec. 4.1: "following EAGLE-2, the draft uses tree
+ * attention with Top-K = 10, total tokens = 60, depth = 7") ----------------------
+ * The paper gives the three numbers only; the growth rule is the one of the
+ * method it follows: a node's value is the sum of the draft's log-probabilities
+ * along its root path; every level expands the Top-K most valuable nodes of the
+ * previous level by their Top-K tokens; at the end the `total` most valuable
+ * candidates form the tree.  Three definitions:
+ *
+ * oracle_topk_logprob: for each row r of logits [R,V] (row stride stride_r),
+ *     lse_r = ln sum_v exp(l_v),
+ *     token[r,0..K-1] = the K tokens of greatest logit, greater first, the lower
+ *                       token first among equal logits,
+ *     score[r,k] = cum[r] + l_{token[r,k]} - lse_r      (cum NULL means 0).
+ * Returns 0, or 5 when K > V.
+ */
+int oracle_topk_logprob(int dtype, int R, int V, int K, const void *logits, int64_t stride_r,
+                        const double *cum, double *score, int32_t *token, double *lse)
+{
+    if (K > V || K < 1) return 5;
+    uint8_t *taken = malloc((size_t)V);
+    if (!taken) return 2;
+    for (int r = 0; r < R; ++r) {
+        const int64_t row = (int64_t)r * stride_r;
+        double mx = -INFINITY;
+        for (int v = 0; v < V; ++v) { double l = elem_as_double(logits, dtype, row + v); if (l > mx) mx = l; }
+        double z = 0.0;
+        for (int v = 0; v < V; ++v) z += exp(elem_as_double(logits, dtype, row + v) - mx);
+        const double l_r = mx + log(z);
+        if (lse) lse[r] = l_r;
+        memset(taken, 0, (size_t)V);
+        for (int k = 0; k < K; ++k) {
+            int best = -1;
+            double bv = 0.0;
+            for (int v = 0; v < V; ++v) {
+                if (taken[v]) continue;
+                const double l = elem_as_double(logits, dtype, row + v);
+                if (best < 0 || l > bv) { best = v; bv = l; }     /* strict: ties keep the lower token */
+            }
+            taken[best] = 1;
+            token[(int64_t)r * K + k] = best;
+            score[(int64_t)r * K + k] = (cum ? cum[r] : 0.0) + bv - l_r;
+        }
+    }
+    free(taken);
+    return 0;
+}
+
+/*
+ * oracle_tree_select: the M most valuable of C scored candidates, per request.
+ * Candidate i beats candidate j when score[i] > score[j], or when the scores are
+ * equal and i < j.  Scores are fp32 values and are compared as they are (this
+ * is a decision, so it is taken on the stored numbers).  sel[b,0..] lists the
+ * winners in increasing candidate index, -1 padded; count[b] = min(M, C_b);
+ * gap[b] (optional) = score of the last winner minus score of the best loser
+ * (+inf when nobody loses).  num_cand NULL means C candidates everywhere.
+ */
+int oracle_tree_select(int B, int C, int M, const float *score, const int32_t *num_cand,
+                       int32_t *sel, int32_t *count, double *gap)
+{
+    for (int b = 0; b < B; ++b) {
+        const int c = num_cand ? num_cand[b] : C;
+        const float *sc = score + (int64_t)b * C;
+        int32_t *out = sel + (int64_t)b * M;
+        int n = 0;
+        double worst_in = INFINITY, best_out = -INFINITY;
+        for (int i = 0; i < c; ++i) {
+            int beaten_by = 0;
+            for (int j = 0; j < c; ++j)
+                if (sc[j] > sc[i] || (sc[j] == sc[i] && j < i)) ++beaten_by;
+            if (beaten_by < M) {
+                out[n++] = i;
+                if ((double)sc[i] < worst_in) worst_in = sc[i];
+            } else if ((double)sc[i] > best_out) {
+                best_out = sc[i];
+            }
+        }
+        for (int j = n; j < M; ++j) out[j] = -1;
+        if (count) count[b] = n;
+        if (gap) gap[b] = best_out == -INFINITY ? INFINITY : worst_in - best_out;
+    }
+    return 0;
+}
+
+/*
+ * oracle_tree_finalize: turn the candidates of a finished growth into the draft
+ * tree that the target verifies.  Candidate i has a score, a token and a parent
+ * candidate cand_parent[i] < i (-1: a child of the root).  The N_max - 1 most
+ * valuable candidates (rule of oracle_tree_select) become nodes 1.., in
+ * increasing candidate index -- which is a topological order because a parent
+ * precedes its children -- and node 0 is the root carrying root_token:
+ *     node_cand[b,j]  candidate behind node j (-1 for the root, -1 padding)
+ *     parent[b,j]     node index of its parent (-1 for the root)
+ *     draft_tok[b,j]  its token
+ *     num_nodes[b]    1 + number of selected candidates
+ * A child never outscores its parent when scores are sums of log-probabilities,
+ * so the selection is closed under "parent of"; returns 4 if it is not, 1 if a
+ * cand_parent entry is not below its own index.
+ */
+int oracle_tree_finalize(int B, int C, int N_max, const float *cand_score, const int32_t *cand_parent,
+                         const int32_t *cand_token, const int32_t *num_cand, const int32_t *root_token,
+                         int32_t *parent, int32_t *draft_tok, int32_t *node_cand, int32_t *num_nodes,
+                         double *gap)
+{
+    const int M = N_max - 1;
+    int32_t *sel = malloc(sizeof(int32_t) * (size_t)(M > 0 ? M : 1));
+    int32_t *node_of = malloc(sizeof(int32_t) * (size_t)(C > 0 ? C : 1));
+    if (!sel || !node_of) { free(sel); free(node_of); return 2; }
+    int rc = 0;
+    for (int b = 0; b < B && !rc; ++b) {
+        const int c = num_cand ? num_cand[b] : C;
+        int32_t cnt = 0;
+        if (M > 0)
+            oracle_tree_select(1, C, M, cand_score + (int64_t)b * C, &c, sel, &cnt, gap ? gap + b : NULL);
+        else if (gap) gap[b] = INFINITY;
+        int32_t *par = parent + (int64_t)b * N_max, *tok = draft_tok + (int64_t)b * N_max;
+        int32_t *nc = node_cand + (int64_t)b * N_max;
+        for (int j = 0; j < N_max; ++j) { par[j] = -1; tok[j] = -1; nc[j] = -1; }
+        for (int i = 0; i < c; ++i) node_of[i] = -1;
+        tok[0] = root_token[b];
+        for (int j = 0; j < cnt; ++j) node_of[sel[j]] = j + 1;
+        for (int j = 0; j < cnt; ++j) {
+            const int i = sel[j];
+            const int cp = cand_parent[(int64_t)b * C + i];
+            if (cp >= i) { rc = 1; break; }
+            if (cp >= 0 && node_of[cp] < 0) { rc = 4; break; }
+            nc[j + 1] = i;
+            par[j + 1] = cp < 0 ? 0 : node_of[cp];
+            tok[j + 1] = cand_token[(int64_t)b * C + i];
+        }
+        num_nodes[b] = cnt + 1;
+    }
+    free(sel); free(node_of);
     return rc;
 }
 
