@@ -52,9 +52,11 @@ typedef enum specvlm_dtype {
 #define SPECVLM_ERR_PATH_TOO_LONG 8  /* an accepted path would not fit in path_cap           */
 #define SPECVLM_ERR_BAD_BLOCK    16  /* block_table entry outside [0, num_blocks)            */
 #define SPECVLM_ERR_BAD_TOKEN    32  /* a drafted token outside [0, V)                       */
+#define SPECVLM_ERR_TREE_NOT_CLOSED 64 /* draft growth: a chosen candidate whose parent was not chosen */
 
 #define SPECVLM_MAX_NODES 64
 #define SPECVLM_PAGE_SIZE 16
+#define SPECVLM_MAX_CANDIDATES 8192  /* draft growth: scored candidates per request */
 
 /*
  * Geometry of one attention layer's tensors.
@@ -221,6 +223,76 @@ int32_t specvlm_kv_compact(const specvlm_attn_desc *desc, int32_t L,
                            const int32_t *block_table_dev, const int32_t *prefix_len_dev,
                            const int32_t *path_dev, int32_t path_cap, const int32_t *accept_len_dev,
                            int32_t *new_prefix_len_dev, int32_t *moved_idx_dev, void *stream);
+
+/*
+ * ---- Draft side: growth of the token tree that the calls above verify ----------------------
+ * Sec. 4.1: following EAGLE-2 the draft grows a tree with Top-K = 10, 60 tokens in total and
+ * depth 7 (Fig. 3: its root is the token the target produced last).  The paper gives the three
+ * numbers; the growth rule is that method's: the value of a candidate node is the sum of the
+ * draft's log-probabilities along its root path; every level expands the most valuable nodes of
+ * the previous level by their Top-K tokens; at the end the most valuable candidates of all
+ * levels form the tree.  One level is specvlm_draft_select (not needed for the root level)
+ * followed by specvlm_draft_topk; specvlm_draft_finalize ends the growth.  The draft model's own
+ * attention over the growing tree is specvlm_tree_verify_attn.
+ *
+ * specvlm_draft_topk: for request b and expanded node w (W per request), over its logits row l:
+ *     lse = ln sum_v exp(l_v)
+ *     token[k] = the K tokens of greatest logit, greater first, the LOWER token first among
+ *                equal logits (values compare as real numbers, -0 == +0; no NaN; finite maximum)
+ *     score[k] = cum[b,w] + (l_token[k] - lse)            (fp32; cum NULL means 0)
+ *     parent[k] = parent_idx[b,w]                          (copied; -1 when parent_idx is NULL)
+ * written to out[b*out_stride_b + w*K + k], so a level can write straight into a request's
+ * candidate arrays.  1 <= K <= min(V, 64).
+ *   logits_dev      device, dtype, element (b,w,v) at b*stride_b + w*stride_w + v
+ *   cum_dev         device fp32, element (b,w) at b*cum_stride_b + w, or NULL
+ *   parent_idx_dev  device int32, element (b,w) at b*parent_stride_b + w, or NULL
+ *   score_out_dev, token_out_dev, parent_out_dev (optional)   device, indexed as above
+ *   lse_out_dev     device fp32 [B, W] or NULL
+ */
+int32_t specvlm_draft_topk(int32_t dtype, int32_t B, int32_t W, int32_t V, int32_t K,
+                           const void *logits_dev, int64_t stride_b, int64_t stride_w,
+                           const float *cum_dev, int64_t cum_stride_b,
+                           const int32_t *parent_idx_dev, int64_t parent_stride_b,
+                           float *score_out_dev, int32_t *token_out_dev, int32_t *parent_out_dev,
+                           int64_t out_stride_b, float *lse_out_dev, void *stream);
+
+/*
+ * The M most valuable of a request's scored candidates: candidate i beats j when
+ * score[i] > score[j], or the scores are equal and i < j (scores are compared as the stored fp32
+ * numbers).  Winners are listed in increasing candidate index.
+ *   score_dev          device fp32, element (b,i) at b*score_stride_b + i, i < C <= SPECVLM_MAX_CANDIDATES
+ *   num_cand_dev       device int32 [B] (clamped to [0, C]) or NULL meaning C
+ *   index_base         added to every listed index (position of the scored range in a larger array)
+ *   sel_out_dev        device int32 [B, M]: winners, then -1
+ *   sel_score_out_dev  device fp32 [B, M] or NULL: their scores, then -inf
+ *   count_out_dev      device int32 [B] or NULL: min(M, num_cand[b])
+ */
+int32_t specvlm_draft_select(int32_t B, int32_t C, int32_t M, const float *score_dev, int64_t score_stride_b,
+                             const int32_t *num_cand_dev, int32_t index_base, int32_t *sel_out_dev,
+                             float *sel_score_out_dev, int32_t *count_out_dev, void *stream);
+
+/*
+ * End of the growth: the N_max - 1 most valuable candidates (rule of specvlm_draft_select) become
+ * tree nodes 1.., in increasing candidate index -- a topological order, because a candidate's
+ * parent cand_parent[i] (< i, or -1 for a child of the root) was created before it -- and node 0
+ * is the root carrying root_token[b]:
+ *     node_cand[b,j]  candidate behind node j (-1 for the root and for padding)
+ *     parent[b,j]     node index of its parent (-1 for the root and for padding)
+ *     draft_tok[b,j]  its token (-1 for padding)
+ *     num_nodes[b]    1 + number of chosen candidates
+ * These are the parent / draft_tok / num_nodes arrays the verification calls take.  Scores that
+ * are sums of log-probabilities never rise from parent to child, so the choice is closed under
+ * "parent of"; if it is not, SPECVLM_ERR_TREE_NOT_CLOSED is set (SPECVLM_ERR_BAD_PARENT for a
+ * cand_parent entry outside [-1, i), SPECVLM_ERR_BAD_NUM_NODES for num_cand outside [0, C]).
+ *   cand_*_dev   device, element (b,i) at b*cand_stride_b + i; C <= SPECVLM_MAX_CANDIDATES
+ *   node_cand_out_dev may be NULL; 1 <= N_max <= 64
+ */
+int32_t specvlm_draft_finalize(int32_t B, int32_t C, int32_t N_max, const float *cand_score_dev,
+                               const int32_t *cand_parent_dev, const int32_t *cand_token_dev,
+                               int64_t cand_stride_b, const int32_t *num_cand_dev,
+                               const int32_t *root_token_dev, int32_t *parent_out_dev,
+                               int32_t *draft_tok_out_dev, int32_t *node_cand_out_dev,
+                               int32_t *num_nodes_out_dev, int32_t *err_flag_dev, void *stream);
 
 #ifdef __cplusplus
 }

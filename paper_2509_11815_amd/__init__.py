@@ -9,6 +9,9 @@ from .binding import (  # noqa: F401
     SpecvlmError,
     lib,
     load_library,
+    specvlm_draft_finalize,
+    specvlm_draft_select,
+    specvlm_draft_topk,
     specvlm_kv_compact,
     specvlm_node_argmax,
     specvlm_tree_accept,

@@ -20,7 +20,7 @@ ERR_BITS = {1: "BAD_PARENT", 2: "BAD_NUM_NODES", 4: "BAD_LENGTH", 8: "PATH_TOO_L
 EXPORTS = ["specvlm_version", "specvlm_last_hip_error", "specvlm_tree_verify_attn_workspace_bytes",
            "specvlm_tree_verify_attn_num_splits",
            "specvlm_tree_verify_attn", "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_tree_accept_sample",
-           "specvlm_kv_compact"]
+           "specvlm_kv_compact", "specvlm_draft_topk", "specvlm_draft_select", "specvlm_draft_finalize"]
 
 
 class SpecvlmError(RuntimeError):
@@ -69,6 +69,12 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.specvlm_tree_accept_sample.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, i64, i64, vp, ctypes.c_float] + [vp] * 8
     L.specvlm_kv_compact.restype = i32
     L.specvlm_kv_compact.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, vp, i64, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    L.specvlm_draft_topk.restype = i32
+    L.specvlm_draft_topk.argtypes = [i32] * 5 + [vp, i64, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp, vp]
+    L.specvlm_draft_select.restype = i32
+    L.specvlm_draft_select.argtypes = [i32, i32, i32, vp, i64, vp, i32, vp, vp, vp, vp]
+    L.specvlm_draft_finalize.restype = i32
+    L.specvlm_draft_finalize.argtypes = [i32, i32, i32, vp, vp, vp, i64] + [vp] * 8
     _lib = L
     return L
 
@@ -276,3 +282,89 @@ def specvlm_kv_compact(k_caches, v_caches, prefix_len, path, accept_len, *, bloc
                                   _ptr(moved_idx), _stream(stream))
     _check(rc, "specvlm_kv_compact")
     return new_prefix_len, moved_idx
+
+
+def _dev_f32(t, name):
+    if t is None:
+        return None
+    if not (t.is_cuda and t.dtype == torch.float32 and t.stride(-1) == 1):
+        raise TypeError(f"{name} must be a float32 device tensor with a contiguous last dimension")
+    return t
+
+
+def specvlm_draft_topk(logits, K, *, cum=None, parent_idx=None, score_out=None, token_out=None, parent_out=None,
+                       lse_out=None, stream=None):
+    """One level of draft-tree growth.  logits [B,W,V]; cum fp32 / parent_idx int32 [B,W] (row strides are
+    taken from the tensors, so they may be views).  Outputs are [B, >= W*K] fp32 / int32 tensors or views
+    (row stride taken from score_out; token_out and parent_out must share it): entry (b, w*K + k).
+    Returns (score_out, token_out, parent_out)."""
+    B, W, V = logits.shape
+    dev = logits.device
+    if logits.stride(2) != 1:
+        raise ValueError("vocab dimension must be contiguous")
+    if score_out is None:
+        score_out = torch.empty((B, W * K), dtype=torch.float32, device=dev)
+    if token_out is None:
+        token_out = torch.empty((B, W * K), dtype=torch.int32, device=dev)
+    if parent_out is None and parent_idx is not None:
+        parent_out = torch.empty((B, W * K), dtype=torch.int32, device=dev)
+    outs = [t for t in (score_out, token_out, parent_out) if t is not None]
+    if any(t.stride(0) != score_out.stride(0) or t.stride(1) != 1 or t.shape[1] < W * K for t in outs):
+        raise ValueError("score_out / token_out / parent_out must share one row stride and hold W*K entries")
+    if token_out.dtype != torch.int32 or (parent_out is not None and parent_out.dtype != torch.int32):
+        raise TypeError("token_out / parent_out must be int32")
+    _dev_f32(score_out, "score_out")
+    rc = lib().specvlm_draft_topk(
+        _dtype_code(logits), B, W, V, K, _ptr(logits), logits.stride(0), logits.stride(1),
+        _ptr(_dev_f32(cum, "cum")), 0 if cum is None else cum.stride(0),
+        _ptr(parent_idx), 0 if parent_idx is None else parent_idx.stride(0),
+        _ptr(score_out), _ptr(token_out), _ptr(parent_out), score_out.stride(0), _ptr(_dev_f32(lse_out, "lse_out")),
+        _stream(stream))
+    _check(rc, "specvlm_draft_topk")
+    return score_out, token_out, parent_out
+
+
+def specvlm_draft_select(score, M, *, num_cand=None, index_base=0, sel_out=None, sel_score_out=None,
+                         count_out=None, stream=None):
+    """score fp32 [B,C] (may be a view of a wider array).  Returns (sel [B,M] int32, sel_score [B,M] fp32,
+    count [B] int32)."""
+    B, C = score.shape
+    dev = score.device
+    _dev_f32(score, "score")
+    if sel_out is None:
+        sel_out = torch.empty((B, M), dtype=torch.int32, device=dev)
+    if sel_score_out is None:
+        sel_score_out = torch.empty((B, M), dtype=torch.float32, device=dev)
+    if count_out is None:
+        count_out = torch.empty(B, dtype=torch.int32, device=dev)
+    rc = lib().specvlm_draft_select(B, C, M, _ptr(score), score.stride(0), _ptr(_dev_i32(num_cand, "num_cand")),
+                                    index_base, _ptr(_dev_i32(sel_out, "sel_out")), _ptr(sel_score_out),
+                                    _ptr(_dev_i32(count_out, "count_out")), _stream(stream))
+    _check(rc, "specvlm_draft_select")
+    return sel_out, sel_score_out, count_out
+
+
+def specvlm_draft_finalize(cand_score, cand_parent, cand_token, root_token, N_max, *, num_cand=None, err_flag=None,
+                           out=None, stream=None):
+    """Candidates [B,C] (fp32 score, int32 parent and token, one row stride) -> (parent [B,N_max],
+    draft_tok [B,N_max], node_cand [B,N_max], num_nodes [B]); `out` may supply these four int32 tensors."""
+    B, C = cand_score.shape
+    dev = cand_score.device
+    _dev_f32(cand_score, "cand_score")
+    for t in (cand_parent, cand_token):
+        if t.dtype != torch.int32 or t.stride() != cand_score.stride():
+            raise ValueError("cand_parent / cand_token must be int32 with cand_score's strides")
+    if out is not None:
+        parent, tok, node_cand, num_nodes = out
+    else:
+        parent = torch.empty((B, N_max), dtype=torch.int32, device=dev)
+        tok = torch.empty((B, N_max), dtype=torch.int32, device=dev)
+        node_cand = torch.empty((B, N_max), dtype=torch.int32, device=dev)
+        num_nodes = torch.empty(B, dtype=torch.int32, device=dev)
+    rc = lib().specvlm_draft_finalize(
+        B, C, N_max, _ptr(cand_score), _ptr(cand_parent), _ptr(cand_token), cand_score.stride(0),
+        _ptr(_dev_i32(num_cand, "num_cand")), _ptr(_dev_i32(root_token, "root_token")),
+        _ptr(_dev_i32(parent, "parent")), _ptr(_dev_i32(tok, "draft_tok")), _ptr(node_cand),
+        _ptr(_dev_i32(num_nodes, "num_nodes")), _ptr(err_flag), _stream(stream))
+    _check(rc, "specvlm_draft_finalize")
+    return parent, tok, node_cand, num_nodes

@@ -65,6 +65,22 @@ int32_t launch_kv_compact(const specvlm_attn_desc& d, int32_t L, void* k_base, v
                           int32_t path_cap, const int32_t* accept_len, int32_t* new_prefix_len,
                           int32_t* moved_idx, hipStream_t stream);
 
+int32_t launch_draft_topk(int32_t dtype, int32_t B, int32_t W, int32_t V, int32_t K, const void* logits,
+                          int64_t stride_b, int64_t stride_w, const float* cum, int64_t cum_stride_b,
+                          const int32_t* parent_idx, int64_t parent_stride_b, float* score_out,
+                          int32_t* token_out, int32_t* parent_out, int64_t out_stride_b, float* lse_out,
+                          hipStream_t stream);
+
+int32_t launch_draft_select(int32_t B, int32_t C, int32_t M, const float* score, int64_t score_stride_b,
+                            const int32_t* num_cand, int32_t index_base, int32_t* sel_out,
+                            float* sel_score_out, int32_t* count_out, hipStream_t stream);
+
+int32_t launch_draft_finalize(int32_t B, int32_t C, int32_t N_max, const float* cand_score,
+                              const int32_t* cand_parent, const int32_t* cand_token, int64_t cand_stride_b,
+                              const int32_t* num_cand, const int32_t* root_token, int32_t* parent_out,
+                              int32_t* draft_tok_out, int32_t* node_cand_out, int32_t* num_nodes_out,
+                              int32_t* err_flag, hipStream_t stream);
+
 struct AttnArgs {
     specvlm_attn_desc d;
     float scale;                // resolved softmax scale

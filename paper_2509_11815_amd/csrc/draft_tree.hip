@@ -1,0 +1,399 @@
+// Draft-side growth of the token tree (SpecVLM Sec. 4.1: the draft grows an EAGLE-2 style tree
+// with Top-K 10, 60 tokens in total, depth 7, which the target then verifies in one pass).
+//
+// The paper gives the three numbers; the rule is the one of the method it follows.  A node's
+// value is the sum of the draft's log-probabilities along its root path.  Every level expands
+// the most valuable nodes of the previous level by their Top-K tokens (draft_topk_kernel),
+// the most valuable new candidates are expanded next (draft_select_kernel), and in the end the
+// most valuable candidates of all levels become the tree (draft_finalize_kernel), numbered in
+// increasing candidate index, which is a topological order because a parent is created before
+// its children.  "More valuable" is: greater stored fp32 score, the lower candidate index among
+// equal scores; Top-K inside a row: greater logit, the lower token among equal logits.
+//
+// All three are latency-bound single-workgroup-per-row kernels: a row of 32000 bf16 logits is
+// 64 KB, a level has at most `width` rows per request, and the candidate lists hold a few
+// hundred entries.
+#include <limits.h>
+
+#include "common.hpp"
+
+namespace specvlm {
+
+namespace {
+
+constexpr int kThreadsDT = 1024;
+constexpr int kWavesDT = kThreadsDT / 64;
+
+template <typename T>
+struct Lane16;
+template <>
+struct Lane16<uint16_t> {
+    static constexpr int kPerVec = 8;
+    __device__ static float at(const uint4& w, int e) {
+        const uint32_t x = (&w.x)[e >> 1];
+        return __uint_as_float((e & 1) ? (x & 0xFFFF0000u) : (x << 16));
+    }
+    __device__ static float one(const uint16_t* p) { return bf16_bits_to_float(*p); }
+};
+template <>
+struct Lane16<float> {
+    static constexpr int kPerVec = 4;
+    __device__ static float at(const uint4& w, int e) { return __uint_as_float((&w.x)[e]); }
+    __device__ static float one(const float* p) { return *p; }
+};
+
+// (logit, token) as one unsigned key whose order is "greater logit, then lower token".
+// -0 and +0 are the same real number and must tie: adding +0 turns -0 into +0.
+__device__ __forceinline__ unsigned long long order_key(float v, int idx) {
+    uint32_t u = __float_as_uint(v + 0.0f);
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return (static_cast<unsigned long long>(u) << 32) | (0xFFFFFFFFu - static_cast<uint32_t>(idx));
+}
+
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const unsigned long long y = __shfl_xor(x, off);
+        x = y > x ? y : x;
+    }
+    return x;
+}
+
+// Fixed-shape workgroup reductions (results never depend on timing).
+__device__ __forceinline__ float wg_max(float x, float* s_red) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = x;
+    __syncthreads();
+    float r = s_red[0];
+#pragma unroll
+    for (int w = 1; w < kWavesDT; ++w) r = fmaxf(r, s_red[w]);
+    return r;
+}
+
+__device__ __forceinline__ float wg_sum(float x, float* s_red) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = x;
+    __syncthreads();
+    float r = s_red[0];
+#pragma unroll
+    for (int w = 1; w < kWavesDT; ++w) r += s_red[w];
+    return r;
+}
+
+// ---------------------------------------------------------------------------------------
+// draft_topk_kernel: one workgroup per (request, expanded node) row.
+//   NS > 0: every thread keeps NS vocabulary entries of the row in registers (16-byte loads
+//           when the row is aligned and V a multiple of the vector width, scalar otherwise);
+//   NS == 0: any vocabulary size, every pass re-reads the row (it stays in L2).
+// Passes: maximum, sum of exp(l - max) (log-sum-exp), then K rounds of a workgroup-wide
+// arg-max over (logit, token) keys.  Every thread caches the best key among its entries not
+// yet taken; only the owner of a round's winner rescans its entries.
+// ---------------------------------------------------------------------------------------
+template <typename T, int NS>
+__global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
+    int V, int K, const T* __restrict__ logits, int64_t stride_b, int64_t stride_w,
+    const float* __restrict__ cum, int64_t cum_stride_b, const int32_t* __restrict__ parent_idx,
+    int64_t parent_stride_b, float* __restrict__ score_out, int32_t* __restrict__ token_out,
+    int32_t* __restrict__ parent_out, int64_t out_stride_b, float* __restrict__ lse_out) {
+    __shared__ float s_red[kWavesDT];
+    __shared__ unsigned long long s_key[2][kWavesDT];
+    __shared__ int s_taken[SPECVLM_MAX_NODES];         // NS == 0: tokens already taken
+
+    const int w = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int nrows = gridDim.x;
+    const T* row = logits + b * stride_b + w * stride_w;
+    constexpr int VEC = Lane16<T>::kPerVec;
+    const bool vec = NS > 0 && (reinterpret_cast<uintptr_t>(row) & 15u) == 0 && V % VEC == 0;   // uniform
+    // entry s of this thread is vocabulary index idx_of(s)
+    auto idx_of = [&](int s) -> int {
+        return vec ? (tid + kThreadsDT * (s / VEC)) * VEC + s % VEC : tid + kThreadsDT * s;
+    };
+    float lv[NS > 0 ? NS : 1];
+    if constexpr (NS > 0) {
+        if (vec) {
+#pragma unroll
+            for (int j = 0; j < NS / VEC; ++j) {
+                const int v0 = (tid + kThreadsDT * j) * VEC;
+                if (v0 < V) {
+                    const uint4 x = *reinterpret_cast<const uint4*>(row + v0);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) lv[j * VEC + e] = Lane16<T>::at(x, e);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) lv[j * VEC + e] = -INFINITY;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const int v = tid + kThreadsDT * s;
+                lv[s] = v < V ? Lane16<T>::one(row + v) : -INFINITY;
+            }
+        }
+    }
+    const int ns_mem = (V + kThreadsDT - 1) / kThreadsDT;          // NS == 0: entries per thread
+
+    // ---- log-sum-exp of the row -----------------------------------------------------------
+    float part = -INFINITY;
+    if constexpr (NS > 0) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) part = fmaxf(part, lv[s]);    // entries past V hold -inf
+    } else {
+#pragma unroll 8
+        for (int s = 0; s < ns_mem; ++s) {
+            const int v = tid + kThreadsDT * s;
+            if (v < V) part = fmaxf(part, Lane16<T>::one(row + v));
+        }
+    }
+    const float mx = wg_max(part, s_red);
+    part = 0.f;
+    if constexpr (NS > 0) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) part += __expf(lv[s] - mx);   // exp(-inf) = 0
+    } else {
+#pragma unroll 8
+        for (int s = 0; s < ns_mem; ++s) {
+            const int v = tid + kThreadsDT * s;
+            if (v < V) part += __expf(Lane16<T>::one(row + v) - mx);
+        }
+    }
+    const float Z = wg_sum(part, s_red);
+    const float lse = mx + logf(Z);
+    const float c = cum ? cum[b * cum_stride_b + w] : 0.f;
+    const int par = parent_idx ? parent_idx[b * parent_stride_b + w] : -1;
+    if (tid == 0 && lse_out) lse_out[b * nrows + w] = lse;
+
+    // ---- K rounds of arg-max ---------------------------------------------------------------
+    unsigned long long taken = 0;                       // NS > 0: bit s = entry s was taken
+    int ntaken = 0;                                     // NS == 0: length of s_taken
+    auto local_best = [&]() -> unsigned long long {
+        unsigned long long best = 0;                    // 0 = nothing left (a real key has bit 63 or 31.. set)
+        if constexpr (NS > 0) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const int v = idx_of(s);
+                if (v < V && !((taken >> s) & 1ull)) {
+                    const unsigned long long k = order_key(lv[s], v);
+                    best = k > best ? k : best;
+                }
+            }
+        } else {
+            for (int s = 0; s < ns_mem; ++s) {
+                const int v = tid + kThreadsDT * s;
+                if (v >= V) break;
+                bool live = true;
+                for (int r = 0; r < ntaken; ++r) live = live && s_taken[r] != v;
+                if (live) {
+                    const unsigned long long k = order_key(Lane16<T>::one(row + v), v);
+                    best = k > best ? k : best;
+                }
+            }
+        }
+        return best;
+    };
+    unsigned long long mine = local_best();
+    const int64_t out0 = b * out_stride_b + static_cast<int64_t>(w) * K;
+    for (int k = 0; k < K; ++k) {
+        const unsigned long long wbest = wave_max_u64(mine);
+        if ((tid & 63) == 0) s_key[k & 1][tid >> 6] = wbest;
+        __syncthreads();                                // (the other buffer was last read two rounds ago)
+        unsigned long long win = s_key[k & 1][0];
+#pragma unroll
+        for (int x = 1; x < kWavesDT; ++x) {
+            const unsigned long long y = s_key[k & 1][x];
+            win = y > win ? y : win;
+        }
+        const int v = static_cast<int>(0xFFFFFFFFu - static_cast<uint32_t>(win));       // K <= V: never empty
+        if constexpr (NS == 0) {
+            if (tid == 0) s_taken[k] = v;
+            ++ntaken;
+            __syncthreads();
+        }
+        if (mine == win) {                              // exactly one thread: tokens are distinct
+            float val;
+            if constexpr (NS > 0) {
+                val = 0.f;
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+                    if (idx_of(s) == v) {
+                        val = lv[s];
+                        taken |= 1ull << s;
+                    }
+            } else {
+                val = Lane16<T>::one(row + v);
+            }
+            token_out[out0 + k] = v;
+            score_out[out0 + k] = c + (val - lse);
+            if (parent_out) parent_out[out0 + k] = par;
+            mine = local_best();
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Ranking of scored candidates: candidate i beats j when score[i] > score[j], or the scores
+// are equal and i < j.  rank(i) = number of candidates that beat i; the M winners are the
+// candidates of rank < M; a winner's position is the number of winners of lower index.
+// s_sc holds the c scores, s_pos (c ints) receives the position of a winner and -1 otherwise.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void rank_winners(const float* s_sc, int* s_pos, int c, int M) {
+    const int tid = threadIdx.x;
+    for (int i = tid; i < c; i += kThreadsDT) {
+        const float si = s_sc[i];
+        int beaten = 0;
+        for (int j = 0; j < c; ++j) {
+            const float sj = s_sc[j];
+            beaten += (sj > si || (sj == si && j < i)) ? 1 : 0;
+        }
+        s_pos[i] = beaten < M ? 1 : 0;
+    }
+    __syncthreads();
+    int pos[(SPECVLM_MAX_CANDIDATES + kThreadsDT - 1) / kThreadsDT];
+    int x = 0;
+    for (int i = tid; i < c; i += kThreadsDT, ++x) {
+        int p = -1;
+        if (s_pos[i]) {
+            p = 0;
+            for (int j = 0; j < i; ++j) p += s_pos[j];
+        }
+        pos[x] = p;
+    }
+    __syncthreads();
+    x = 0;
+    for (int i = tid; i < c; i += kThreadsDT, ++x) s_pos[i] = pos[x];
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(kThreadsDT) void draft_select_kernel(
+    int C, int M, const float* __restrict__ score, int64_t score_stride_b, const int32_t* __restrict__ num_cand,
+    int index_base, int32_t* __restrict__ sel_out, float* __restrict__ sel_score_out,
+    int32_t* __restrict__ count_out) {
+    extern __shared__ unsigned char s_dyn[];
+    float* s_sc = reinterpret_cast<float*>(s_dyn);
+    int* s_pos = reinterpret_cast<int*>(s_dyn) + C;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int c = num_cand ? min(max(num_cand[b], 0), C) : C;
+    for (int i = tid; i < c; i += kThreadsDT) s_sc[i] = score[b * score_stride_b + i];
+    __syncthreads();
+    rank_winners(s_sc, s_pos, c, M);
+    const int count = min(M, c);
+    for (int i = tid; i < c; i += kThreadsDT) {
+        const int p = s_pos[i];
+        if (p >= 0) {
+            sel_out[b * M + p] = i + index_base;
+            if (sel_score_out) sel_score_out[b * M + p] = s_sc[i];
+        }
+    }
+    for (int p = count + tid; p < M; p += kThreadsDT) {
+        sel_out[b * M + p] = -1;
+        if (sel_score_out) sel_score_out[b * M + p] = -INFINITY;
+    }
+    if (tid == 0 && count_out) count_out[b] = count;
+}
+
+__global__ __launch_bounds__(kThreadsDT) void draft_finalize_kernel(
+    int C, int N_max, const float* __restrict__ cand_score, const int32_t* __restrict__ cand_parent,
+    const int32_t* __restrict__ cand_token, int64_t cand_stride_b, const int32_t* __restrict__ num_cand,
+    const int32_t* __restrict__ root_token, int32_t* __restrict__ parent_out, int32_t* __restrict__ draft_tok_out,
+    int32_t* __restrict__ node_cand_out, int32_t* __restrict__ num_nodes_out, int32_t* __restrict__ err_flag) {
+    extern __shared__ unsigned char s_dyn[];
+    float* s_sc = reinterpret_cast<float*>(s_dyn);
+    int* s_pos = reinterpret_cast<int*>(s_dyn) + C;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    int err = 0;
+    int c = num_cand ? num_cand[b] : C;
+    if (c < 0 || c > C) {
+        err |= SPECVLM_ERR_BAD_NUM_NODES;
+        c = min(max(c, 0), C);
+    }
+    const int M = N_max - 1;
+    const int64_t base = b * cand_stride_b;
+    for (int i = tid; i < c; i += kThreadsDT) s_sc[i] = cand_score[base + i];
+    __syncthreads();
+    rank_winners(s_sc, s_pos, c, M);
+    const int count = min(M, c);
+    for (int i = tid; i < c; i += kThreadsDT) {
+        const int p = s_pos[i];
+        if (p < 0) continue;
+        const int cp = cand_parent[base + i];
+        int pn = -1;
+        if (cp < -1 || cp >= i) {
+            err |= SPECVLM_ERR_BAD_PARENT;
+        } else if (cp < 0) {
+            pn = 0;
+        } else if (s_pos[cp] < 0) {
+            err |= SPECVLM_ERR_TREE_NOT_CLOSED;         // a chosen candidate whose parent was not chosen
+        } else {
+            pn = s_pos[cp] + 1;
+        }
+        const int node = p + 1;
+        parent_out[b * N_max + node] = pn;
+        draft_tok_out[b * N_max + node] = cand_token[base + i];
+        if (node_cand_out) node_cand_out[b * N_max + node] = i;
+    }
+    for (int node = count + 1 + tid; node < N_max; node += kThreadsDT) {
+        parent_out[b * N_max + node] = -1;
+        draft_tok_out[b * N_max + node] = -1;
+        if (node_cand_out) node_cand_out[b * N_max + node] = -1;
+    }
+    if (tid == 0) {
+        parent_out[b * N_max] = -1;
+        draft_tok_out[b * N_max] = root_token[b];
+        if (node_cand_out) node_cand_out[b * N_max] = -1;
+        num_nodes_out[b] = count + 1;
+    }
+    if (err && err_flag) atomicOr(err_flag, err);
+}
+
+}  // namespace
+
+int32_t launch_draft_topk(int32_t dtype, int32_t B, int32_t W, int32_t V, int32_t K, const void* logits,
+                          int64_t stride_b, int64_t stride_w, const float* cum, int64_t cum_stride_b,
+                          const int32_t* parent_idx, int64_t parent_stride_b, float* score_out,
+                          int32_t* token_out, int32_t* parent_out, int64_t out_stride_b, float* lse_out,
+                          hipStream_t stream) {
+    const dim3 grid(W, B), block(kThreadsDT);
+#define SPECVLM_LAUNCH_TK(T, NS)                                                                               \
+    hipLaunchKernelGGL((draft_topk_kernel<T, NS>), grid, block, 0, stream, V, K, static_cast<const T*>(logits), \
+                       stride_b, stride_w, cum, cum_stride_b, parent_idx, parent_stride_b, score_out,          \
+                       token_out, parent_out, out_stride_b, lse_out)
+    const int per_thread = (V + kThreadsDT - 1) / kThreadsDT;
+    if (dtype == SPECVLM_BF16) {
+        if (per_thread <= 32) SPECVLM_LAUNCH_TK(uint16_t, 32);
+        else if (per_thread <= 64) SPECVLM_LAUNCH_TK(uint16_t, 64);
+        else SPECVLM_LAUNCH_TK(uint16_t, 0);
+    } else {
+        if (per_thread <= 32) SPECVLM_LAUNCH_TK(float, 32);
+        else if (per_thread <= 64) SPECVLM_LAUNCH_TK(float, 64);
+        else SPECVLM_LAUNCH_TK(float, 0);
+    }
+#undef SPECVLM_LAUNCH_TK
+    return check_launch();
+}
+
+int32_t launch_draft_select(int32_t B, int32_t C, int32_t M, const float* score, int64_t score_stride_b,
+                            const int32_t* num_cand, int32_t index_base, int32_t* sel_out,
+                            float* sel_score_out, int32_t* count_out, hipStream_t stream) {
+    const size_t lds = static_cast<size_t>(C) * 8;
+    hipLaunchKernelGGL(draft_select_kernel, dim3(B), dim3(kThreadsDT), lds, stream, C, M, score, score_stride_b,
+                       num_cand, index_base, sel_out, sel_score_out, count_out);
+    return check_launch();
+}
+
+int32_t launch_draft_finalize(int32_t B, int32_t C, int32_t N_max, const float* cand_score,
+                              const int32_t* cand_parent, const int32_t* cand_token, int64_t cand_stride_b,
+                              const int32_t* num_cand, const int32_t* root_token, int32_t* parent_out,
+                              int32_t* draft_tok_out, int32_t* node_cand_out, int32_t* num_nodes_out,
+                              int32_t* err_flag, hipStream_t stream) {
+    const size_t lds = static_cast<size_t>(C) * 8;
+    hipLaunchKernelGGL(draft_finalize_kernel, dim3(B), dim3(kThreadsDT), lds, stream, C, N_max, cand_score,
+                       cand_parent, cand_token, cand_stride_b, num_cand, root_token, parent_out, draft_tok_out,
+                       node_cand_out, num_nodes_out, err_flag);
+    return check_launch();
+}
+
+}  // namespace specvlm

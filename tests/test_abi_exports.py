@@ -49,3 +49,8 @@ def test_host_side_argument_checks_need_no_gpu():
     assert rc == 1                                                                      # INVALID_ARG
     assert lib.specvlm_node_argmax(0, 1, 65, 10, null, 0, 10, null, null, null) == 1
     assert lib.specvlm_tree_accept(1, 8, 0, *([null] * 10)) == 1
+    # draft-side growth: K > V, K > 64, too many candidates, N_max > 64
+    assert lib.specvlm_draft_topk(0, 1, 1, 10, 11, *([null, 0, 10] + [null, 0] * 2 + [null] * 3 + [11, null, null])) == 1
+    assert lib.specvlm_draft_topk(0, 1, 1, 100, 65, *([null, 0, 100] + [null, 0] * 2 + [null] * 3 + [65, null, null])) == 1
+    assert lib.specvlm_draft_select(1, 8193, 4, null, 8193, null, 0, null, null, null, null) == 1
+    assert lib.specvlm_draft_finalize(1, 100, 65, null, null, null, 100, *([null] * 8)) == 1
