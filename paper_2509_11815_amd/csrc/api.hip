@@ -19,6 +19,7 @@ static int32_t check_kv_geometry(const specvlm_attn_desc& d) {
     if (d.kv_stride_t < d.D || d.kv_stride_t % vec || d.kv_stride_h % vec || d.kv_stride_b % vec)
         return SPECVLM_INVALID_ARG;
     if (d.kv_stride_h < 0 || d.kv_stride_b < 0) return SPECVLM_INVALID_ARG;
+    if (d.kv_stride_t > (1 << 24)) return SPECVLM_INVALID_ARG;       // lane offsets inside a tile are 32-bit
     if (d.paged) {
         if (d.block_size != SPECVLM_PAGE_SIZE || d.max_blocks_per_req < 1 || d.num_blocks < 1)
             return SPECVLM_INVALID_ARG;

@@ -5,12 +5,16 @@
 //
 //   grid      one workgroup (8 wavefronts, two per SIMD) per (request, query head, split).
 //             A workgroup runs 2 independent key "streams"; stream s of the 2*splits streams
-//             of a (request, head) owns the 32-key tiles s, s + 2*splits, ...  Four wavefronts
+//             of a (request, head) owns the 32-key tiles s, s + 2*splits, ... (neighbouring
+//             streams read neighbouring memory: measured 5 % faster than one contiguous chunk
+//             per stream; a step costs the same whatever part of its tile is real, so cutting
+//             the last round into equal shorter spans gained nothing).  Four wavefronts
 //             share a stream: each takes 16 of the 64 query rows, so a K/V byte is fetched
 //             from HBM exactly once and read from LDS four times.  Two wavefronts per SIMD
 //             let one's matrix work overlap the other's softmax arithmetic and LDS latency
 //   fetch     every stream keeps a private four-slot LDS ring filled by direct-to-LDS loads
-//             (global_load_lds_dwordx4: no registers are tied up by bytes in flight); one load
+//             (global_load_lds_dwordx4, non-temporal since the bytes are used once: no registers
+//             are tied up by bytes in flight); one load
 //             instruction moves four whole 256-byte rows, fully coalesced.  Each wavefront of
 //             a stream requests 8 of a tile's 32 rows.  Two tiles per stream are in flight
 //             ahead of the one consumed: about 64 load instructions per compute unit, which
@@ -85,9 +89,17 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // travels in M0).  The compiler does not see the LDS write: every consumer sits behind
 // wait_vmcnt<>() below, which is also a compiler memory barrier.
 __device__ __forceinline__ void dma16(const void* gsrc, uint32_t lds_dst) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
                  :
                  : "v"(gsrc), "s"(lds_dst)
+                 : "memory");
+}
+
+// Same with a wavefront-uniform base address and a 32-bit lane offset in bytes.
+__device__ __forceinline__ void dma16s(const void* sbase, uint32_t voff, uint32_t lds_dst) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(lds_dst)
                  : "memory");
 }
 
@@ -187,16 +199,14 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     n = min(max(n, 1), p.N_max);
     if (P < 0 || P + n > p.g.capacity) err |= SPECVLM_ERR_BAD_LENGTH;
     const int S = P + n;
-    const int ntile = (S + kTile - 1) / kTile;                       // 32-key tiles of this request
     const int nstream = kStreams * p.num_splits;
     const int stream = split * kStreams + st;
+    const int ntile = (S + kTile - 1) / kTile;                       // 32-key tiles of this request
     // tiles stream, stream + nstream, ... ; none when the lengths are bad (nothing may be fetched then)
     const int my_tiles = (!err && stream < ntile) ? (ntile - stream + nstream - 1) / nstream : 0;
     // the workgroup's first stream has the most tiles: the (uniform) trip count of the main loop
     const int wg_tiles = (!err && split * kStreams < ntile) ? (ntile - split * kStreams + nstream - 1) / nstream : 0;
 
-    const uint16_t* kbase = p.k + hk * p.g.stride_h;
-    const uint16_t* vbase = p.v + hk * p.g.stride_h;
     unsigned char* ring = s_ring + st * kRingBytes;
     typedef __attribute__((address_space(3))) unsigned char lds_byte;
     const uint32_t ring_lds = (uint32_t)(uintptr_t)(lds_byte*)ring;      // LDS byte address of the ring
@@ -204,50 +214,56 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     // ---- tile fetch ------------------------------------------------------------------------
     // Load instruction i of a tile moves rows RPI*i .. RPI*i+RPI-1: lane -> (row, LDS granule
     // position); for K the lane fetches global granule position^(row % ROWG), so the tile
-    // lands XOR-swizzled.  Rows past the request's end are clamped to its last row.
+    // lands XOR-swizzled.  The address of a load is a wavefront-uniform 64-bit base (the first
+    // row of the group, on the scalar ALU) plus a 32-bit lane offset that never changes (row
+    // within the group, granule), so a refill costs a handful of scalar instructions; only a
+    // group that reaches past the request's last key takes the slow path, where rows past that
+    // key re-read its row (finite data that gets weight zero).
     const int lrow = lane / ROWG, lpos = lane % ROWG;
-    const int64_t lane_row_off = static_cast<int64_t>(lrow) * p.g.stride_t;
-    const int last_group = ((S - 1) / RPI) * RPI;          // first row of the last RPI-row group with a real row
+    const uint32_t row_bytes = static_cast<uint32_t>(p.g.stride_t) * 2u;      // (checked on the host: fits easily)
+    uint32_t voff_k[KPW];                                  // lane offset of K load ii of this wavefront
+#pragma unroll
+    for (int ii = 0; ii < KPW; ++ii)
+        voff_k[ii] = lrow * row_bytes + (lpos ^ (((qw * KPW + ii) * RPI + lrow) & (ROWG - 1))) * 16;
+    const uint32_t voff_v = lrow * row_bytes + lpos * 16;
     // Paged cache: physical ids of the two 16-key blocks of a tile, through the scalar cache.
     // They are looked up one tile ahead of the loads that need them, so the look-up latency
     // never sits between a free ring slot and its refill.
-    const int last_blk = (S - 1) >> 4;
-    auto fetch_blocks = [&](int tile, int (&phys)[2]) {
+    auto fetch_blocks = [&](int j, int (&phys)[2]) {
         if (!p.g.block_table) return;
+        const int blk0 = (stream + j * nstream) * (kTile >> 4), last_blk = (S - 1) >> 4;
 #pragma unroll
         for (int x = 0; x < 2; ++x)
-            phys[x] = ((const_i32)p.g.block_table)[static_cast<int64_t>(b) * p.g.max_blocks + min(tile * 2 + x, last_blk)];
+            phys[x] = ((const_i32)p.g.block_table)[static_cast<int64_t>(b) * p.g.max_blocks + min(blk0 + x, last_blk)];
     };
-    // Element offset (from kbase / vbase) of this lane's row for load instruction i of `tile`.
-    // Everything but the last addition is wavefront-uniform (scalar ALU).
-    auto row_offset = [&](int tile, int i, const int (&phys)[2]) -> int64_t {
-        const int r0 = min(tile * kTile + i * RPI, last_group);         // uniform: first row of the group
-        int64_t base;
-        if (p.g.block_table) {
-            // the group's block is block (i*RPI)/16 of the tile, or the request's last block when clamped
-            const int id = min(max(phys[(i * RPI) >> 4], 0), p.g.num_blocks - 1);
-            base = id * p.g.stride_b + (r0 & 15) * p.g.stride_t;
-        } else {
-            base = b * p.g.stride_b + static_cast<int64_t>(r0) * p.g.stride_t;
-        }
-        if (r0 + RPI <= S) return base + lane_row_off;                  // uniform test: every row is real
-        return base + static_cast<int64_t>(min(lrow, S - 1 - r0)) * p.g.stride_t;
-    };
+    const int64_t head_off = hk * p.g.stride_h + (p.g.block_table ? 0 : b * p.g.stride_b);   // elements
     // A wavefront requests its 32/WQ rows of the stream's tile, K and V: KPW loads each, into the
     // two areas of the slot that only this wavefront ever fills.
     const uint32_t area = qw * KPW * 1024;                // this wavefront's area inside a K (or V) tile
     auto issue_part = [&](int j, const int (&phys)[2]) {
-        const int tile = stream + j * nstream;
         const uint32_t dst = ring_lds + (j % kSlots) * kSlotBytes;
+        const int lo = (stream + j * nstream) * kTile, lim = S;          // first key, and the request's end
 #pragma unroll
         for (int ii = 0; ii < KPW; ++ii) {
             const int i = qw * KPW + ii;
-            dma16(kbase + row_offset(tile, i, phys) + (lpos ^ ((i * RPI + lrow) & (ROWG - 1))) * 8, dst + i * 1024);
-        }
-#pragma unroll
-        for (int ii = 0; ii < KPW; ++ii) {
-            const int i = qw * KPW + ii;
-            dma16(vbase + row_offset(tile, i, phys) + lpos * 8, dst + kTileBytes + i * 1024);
+            int r0 = lo + i * RPI;                         // uniform: first row of the group
+            uint32_t vk = voff_k[ii], vv = voff_v;
+            if (r0 + RPI > lim) {                          // uniform, rare: some row of the group is not real
+                r0 = min(r0, ((lim - 1) / RPI) * RPI);     // the last group with a real row
+                const uint32_t rl = min(lrow, lim - 1 - r0) * row_bytes;
+                vk = rl + (lpos ^ ((i * RPI + lrow) & (ROWG - 1))) * 16;
+                vv = rl + lpos * 16;
+            }
+            int64_t base = head_off;                       // elements, uniform
+            if (p.g.block_table) {
+                // the group's block is block (i*RPI)/16 of the tile, or the request's last block when clamped
+                const int id = min(max(phys[(i * RPI) >> 4], 0), p.g.num_blocks - 1);
+                base += id * p.g.stride_b + (r0 & 15) * p.g.stride_t;
+            } else {
+                base += static_cast<int64_t>(r0) * p.g.stride_t;
+            }
+            dma16s(p.k + base, vk, dst + i * 1024);
+            dma16s(p.v + base, vv, dst + kTileBytes + i * 1024);
         }
     };
     typedef __attribute__((address_space(3))) int lds_int;
@@ -264,7 +280,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         dma4(p.parent + static_cast<int64_t>(b) * p.N_max + min(lane, p.N_max - 1),
              (uint32_t)(uintptr_t)(lds_int*)s_par);
     int phys[2] = {0, 0};
-    if (my_tiles > 0) { fetch_blocks(stream, phys); issue_part(0, phys); }
+    if (my_tiles > 0) { fetch_blocks(0, phys); issue_part(0, phys); }
     constexpr uint32_t kStage = (kSlots - 1) * kSlotBytes;
 #pragma unroll
     for (int i = 0; i < 2 * KPW; ++i) {
@@ -275,8 +291,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     }
 #pragma unroll
     for (int t = 1; t < PD; ++t)
-        if (t < my_tiles) { fetch_blocks(stream + t * nstream, phys); issue_part(t, phys); }
-    if (PD < my_tiles) fetch_blocks(stream + PD * nstream, phys);
+        if (t < my_tiles) { fetch_blocks(t, phys); issue_part(t, phys); }
+    if (PD < my_tiles) fetch_blocks(PD, phys);
 
     // waits until at most c tiles' worth (NI instructions each; the query rows are NI too) of this
     // wavefront's loads are outstanding (c uniform, <= PD)
@@ -353,7 +369,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         // About 64 load instructions in flight per compute unit is what the memory pipeline
         // takes without stalling the issuing wavefront.
         if (j + PD < my_tiles) issue_part(j + PD, phys);
-        if (j + PD + 1 < my_tiles) fetch_blocks(stream + (j + PD + 1) * nstream, phys);     // for the next iteration
+        if (j + PD + 1 < my_tiles) fetch_blocks(j + PD + 1, phys);     // for the next iteration
 
         if (j < my_tiles) {
         // K fragments of the tile (A operand): lane (key = 16x + l16, g) holds d = 32c + 8g .. +7
