@@ -576,35 +576,58 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     }
     __syncthreads();
     if (!s_flag || !wave_active) return;
-    // acquire: drop whatever this compute unit / L2 may still hold of the workspace from earlier calls
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    // The partials are read with device-coherent loads (the encoding of an agent-scope atomic load:
+    // they never return what this compute unit or its L2 still holds of the workspace from
+    // earlier calls), issued after the ticket was seen; this is cheaper than an acquire fence,
+    // which would also invalidate the L2.  The compiler does not track these loads: load_batch
+    // waits for them itself and passes the registers through an empty asm, so that no use can
+    // be scheduled before the wait.
+    auto ld16 = [](const u32x4* a) {
+        u32x4 v;
+        asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(a) : "memory");
+        return v;
+    };
+    auto ld8 = [](const float2* a) {
+        f32x2 v;
+        asm volatile("global_load_dwordx2 %0, %1, off sc1" : "=v"(v) : "v"(a) : "memory");
+        return v;
+    };
     const float2* mlp = reinterpret_cast<const float2*>(p.ws_ml) + part0 * kQRows + qi;
     const u32x4* accp = reinterpret_cast<const u32x4*>(p.ws_acc) + (part0 * 4 + q4) * PV4 * 64 + lane;
-    // splits are taken 8 at a time with every load of a batch issued before the first use;
-    // indices past the last split are clamped and given weight zero, so there is no branch
     const int last = p.num_splits - 1;
     // Splits are taken 8 at a time, every load of a batch issued before its first use; indices
     // past the last split are clamped and given weight zero, so there is no branch.  The first
     // batch is requested together with the reference maxima it will be weighted by.
     u32x4 part[8][PV4];
-    float2 ml[8];
+    f32x2 ml[8];
     auto load_batch = [&](int s0) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int64_t se = min(s0 + u, last);
-            ml[u] = mlp[se * kQRows];
+            ml[u] = ld8(mlp + se * kQRows);
 #pragma unroll
-            for (int v = 0; v < PV4; ++v) part[u][v] = accp[(se * 4 * PV4 + v) * 64];
+            for (int v = 0; v < PV4; ++v) part[u][v] = ld16(accp + (se * 4 * PV4 + v) * 64);
+        }
+        wait_vmcnt<0>();
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            asm volatile("" : "+v"(ml[u]));
+#pragma unroll
+            for (int v = 0; v < PV4; ++v) asm volatile("" : "+v"(part[u][v]));
         }
     };
     load_batch(0);
     float Mall = -INFINITY;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) Mall = fmaxf(Mall, ml[u].x);
+    for (int u = 0; u < 8; ++u) Mall = fmaxf(Mall, ml[u][0]);
     for (int s0 = 8; s0 < p.num_splits; s0 += 8) {
         float mv[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) mv[u] = mlp[min(s0 + u, last) * kQRows].x;
+        for (int u = 0; u < 8; ++u) {
+            f32x2 t2 = ld8(mlp + min(s0 + u, last) * kQRows);
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(t2) : : "memory");
+            mv[u] = t2[0];
+        }
 #pragma unroll
         for (int u = 0; u < 8; ++u) Mall = fmaxf(Mall, mv[u]);
     }
@@ -616,8 +639,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         if (s0 > 0) load_batch(s0);
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const float w = s0 + u <= last ? fast_exp2((ml[u].x - m_safe) * c2) : 0.f;
-            Lall += ml[u].y * w;
+            const float w = s0 + u <= last ? fast_exp2((ml[u][0] - m_safe) * c2) : 0.f;
+            Lall += ml[u][1] * w;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
