@@ -134,6 +134,27 @@ def node_argmax(logits, num_nodes=None):
     return amax
 
 
+def head_argmax(hidden, W, num_nodes=None):
+    """hidden [B,N_max,E], W [V,E] (uint16 bf16 bits or float32, same type).  Returns
+    (amax [B,N_max] int32, max_logit [B,N_max] float64, gap [B,N_max] float64, second [B,N_max] int32)."""
+    dt = _dtype_code(hidden)
+    assert _dtype_code(W) == dt
+    B, N_max, E = hidden.shape
+    V = W.shape[0]
+    assert W.shape[1] == E and hidden.strides[2] == hidden.itemsize and W.strides[1] == W.itemsize
+    hs, ws = _estrides(hidden), _estrides(W)
+    nn = None if num_nodes is None else _i32(num_nodes)
+    amax = np.zeros((B, N_max), dtype=np.int32)
+    mx = np.zeros((B, N_max), dtype=np.float64)
+    gap = np.zeros((B, N_max), dtype=np.float64)
+    second = np.zeros((B, N_max), dtype=np.int32)
+    I64 = ctypes.c_int64
+    _load().oracle_head_argmax(ctypes.c_int(dt), ctypes.c_int(B), ctypes.c_int(N_max), ctypes.c_int(E),
+                               ctypes.c_int(V), _p(hidden), I64(hs[0]), I64(hs[1]), _p(W), I64(ws[0]), _p(nn),
+                               _p(amax), _p(mx), _p(gap), _p(second))
+    return amax, mx, gap, second
+
+
 def tree_accept(parent, draft_tok, amax, num_nodes=None, path_cap=8):
     """Returns (accept_len [B], path [B,path_cap], bonus_tok [B], committed_tok [B,path_cap])."""
     parent = _i32(parent)

@@ -21,6 +21,8 @@
  *                         (speculative sampling with fixed candidates)
  *   oracle_kv_compact     move the accepted path's K/V rows to the front of
  *                         the tree region (read-all-then-write)
+ *   oracle_head_argmax    the output head applied to the nodes' hidden states, fused
+ *                         with the greedy choice (the logits are never stored)
  *   oracle_topk_logprob, oracle_tree_select, oracle_tree_finalize
  *                         the draft side: Top-K expansion of a level, choice of
  *                         the next level's nodes, and the final tree
@@ -35,7 +37,9 @@
  * growth, a hand-worked fixture, scipy's log_softmax / logsumexp and numpy's
  * stable sort, closed forms (uniform logits, probabilities summing to one) and
  * enumeration of all token sequences (an exhaustively expanded tree must hold
- * exactly the most probable sequences).
+ * exactly the most probable sequences); for the fused head, numpy's float64 matmul
+ * + argmax, one-hot head rows, integer-valued inputs whose fp32 logits are exact
+ * (then it must agree with oracle_node_argmax on the stored logits) and duplicate rows.
  *
  * Only tests/, the smoke check and the benchmark's cpu_baseline leg may call
  * this file.  It shares no code with the HIP library.
@@ -545,6 +549,59 @@ int oracle_tree_finalize(int B, int C, int N_max, const float *cand_score, const
     }
     free(sel); free(node_of);
     return rc;
+}
+
+/*
+ * ---- output head fused with the greedy choice (Fig. 3: the output head is shared by target and
+ * draft; temperature 0, Sec. 4.1) ----------------------------------------------------------------
+ * The target's logits of node i are the head matrix applied to its last hidden state,
+ *     logit[b,i,v] = sum_e hidden[b,i,e] * W[v,e]                     (W is [V,E], row v = token v)
+ * and the greedy token is amax[b,i] = the lowest v holding the row's greatest logit.  This is
+ * oracle_node_argmax applied to logits that are never stored.  Everything in double (products of
+ * bf16 or fp32 inputs are exact in double; the sum is rounded as double).  Optional outputs:
+ *     max_logit[b,i]  the greatest logit
+ *     gap[b,i]        greatest minus second greatest logit over DIFFERENT tokens (0 on an exact tie,
+ *                     +inf when V == 1): a comparison partner that accumulates in lower precision
+ *                     can only be held to rows whose gap exceeds its rounding error
+ *     second[b,i]     the token holding the second greatest logit (lowest index on ties), -1 if V == 1
+ * Rows i >= num_nodes[b] get amax -1.  hidden element (b,i,e) at b*h_stride_b + i*h_stride_n + e.
+ */
+int oracle_head_argmax(int dtype, int B, int N_max, int E, int V, const void *hidden, int64_t h_stride_b,
+                       int64_t h_stride_n, const void *W, int64_t w_stride_v, const int32_t *num_nodes,
+                       int32_t *amax, double *max_logit, double *gap, int32_t *second)
+{
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b)
+        for (int i = 0; i < N_max; ++i) {
+            const int64_t o = (int64_t)b * N_max + i;
+            const int n = num_nodes ? num_nodes[b] : N_max;
+            if (i >= n) {
+                amax[o] = -1;
+                if (max_logit) max_logit[o] = 0.0;
+                if (gap) gap[o] = INFINITY;
+                if (second) second[o] = -1;
+                continue;
+            }
+            const int64_t h0 = (int64_t)b * h_stride_b + (int64_t)i * h_stride_n;
+            int best = -1, sec = -1;
+            double bv = 0.0, sv = 0.0;
+            for (int v = 0; v < V; ++v) {
+                double acc = 0.0;
+                for (int e = 0; e < E; ++e)
+                    acc += elem_as_double(hidden, dtype, h0 + e) * elem_as_double(W, dtype, (int64_t)v * w_stride_v + e);
+                if (best < 0 || acc > bv) {            /* strict: ties keep the lower token */
+                    sec = best; sv = bv;
+                    best = v; bv = acc;
+                } else if (sec < 0 || acc > sv) {
+                    sec = v; sv = acc;
+                }
+            }
+            amax[o] = best;
+            if (max_logit) max_logit[o] = bv;
+            if (gap) gap[o] = sec < 0 ? INFINITY : bv - sv;
+            if (second) second[o] = sec;
+        }
+    return 0;
 }
 
 /*
