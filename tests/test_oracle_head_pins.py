@@ -61,6 +61,10 @@ def test_exact_integer_case_agrees_with_argmax_of_stored_logits(oracle):
     assert (gap == 0).any() and np.all(gap >= 0)                         # integer logits tie often
     tie = gap == 0
     assert np.all(second[tie] > amax[tie])                               # the lower token wins a tie
+    for bb in range(B):                                                  # runner-up: same rule among the rest
+        for i in range(N):
+            order = np.lexsort((np.arange(V), -logits[bb, i].astype(np.float64)))
+            assert second[bb, i] == order[1]
     hb, wb = W.f32_to_bf16_bits(h), W.f32_to_bf16_bits(w)                # the same numbers as bf16
     assert np.array_equal(oracle.head_argmax(hb, wb)[0], amax)
 
