@@ -225,6 +225,32 @@ int32_t specvlm_kv_compact(const specvlm_attn_desc *desc, int32_t L,
                            int32_t *new_prefix_len_dev, int32_t *moved_idx_dev, void *stream);
 
 /*
+ * Output head fused with the greedy choice (Fig. 3: target and draft share one output head;
+ * Sec. 4.1: temperature 0).  Replaces "project to logits, store them, specvlm_node_argmax":
+ *     logit[b,i,v] = sum_e hidden[b,i,e] * W[v,e]          (bf16 products, fp32 accumulation)
+ *     amax[b,i]    = the LOWEST v whose logit is the row's greatest (-0 == +0; inputs finite)
+ * The [nodes, vocabulary] logits are never stored and W is streamed from HBM once per block of 64
+ * node rows.  The choice is taken on the fp32 sums, so against exact arithmetic it can differ
+ * only where the two greatest logits of a row are closer than the fp32 accumulation error.
+ * Rows i >= num_nodes[b] get amax -1 (their hidden rows are still read and must be finite memory).
+ *   dtype          SPECVLM_BF16 only (SPECVLM_F32 returns SPECVLM_UNSUPPORTED)
+ *   hidden_dev     device bf16, element (b,i,e) at b*h_stride_b + i*h_stride_n + e, with
+ *                  h_stride_b == N_max*h_stride_n; rows 16-byte aligned; E a multiple of 128
+ *   w_dev          device bf16 [V, E], row v at v*w_stride_v (the layout of a linear layer's weight)
+ *   amax_dev       device int32 [B, N_max]
+ *   max_logit_dev  device fp32 [B, N_max] or NULL: the greatest logit (0 for rows past num_nodes)
+ *   workspace_dev  specvlm_head_argmax_workspace_bytes(B, N_max, V) bytes, 256-byte aligned,
+ *                  ZERO-FILLED ONCE after allocation (every call leaves its counters zero);
+ *                  calls that may run concurrently need separate workspaces
+ */
+size_t specvlm_head_argmax_workspace_bytes(int32_t B, int32_t N_max, int32_t V);
+int32_t specvlm_head_argmax(int32_t dtype, int32_t B, int32_t N_max, int32_t E, int32_t V,
+                            const void *hidden_dev, int64_t h_stride_b, int64_t h_stride_n,
+                            const void *w_dev, int64_t w_stride_v, const int32_t *num_nodes_dev,
+                            int32_t *amax_dev, float *max_logit_dev,
+                            void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/*
  * ---- Draft side: growth of the token tree that the calls above verify ----------------------
  * Sec. 4.1: following EAGLE-2 the draft grows a tree with Top-K = 10, 60 tokens in total and
  * depth 7 (Fig. 3: its root is the token the target produced last).  The paper gives the three

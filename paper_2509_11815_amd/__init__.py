@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     specvlm_draft_finalize,
     specvlm_draft_select,
     specvlm_draft_topk,
+    specvlm_head_argmax,
+    specvlm_head_argmax_workspace_bytes,
     specvlm_kv_compact,
     specvlm_node_argmax,
     specvlm_tree_accept,

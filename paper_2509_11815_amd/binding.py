@@ -20,7 +20,8 @@ ERR_BITS = {1: "BAD_PARENT", 2: "BAD_NUM_NODES", 4: "BAD_LENGTH", 8: "PATH_TOO_L
 EXPORTS = ["specvlm_version", "specvlm_last_hip_error", "specvlm_tree_verify_attn_workspace_bytes",
            "specvlm_tree_verify_attn_num_splits",
            "specvlm_tree_verify_attn", "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_tree_accept_sample",
-           "specvlm_kv_compact", "specvlm_draft_topk", "specvlm_draft_select", "specvlm_draft_finalize"]
+           "specvlm_kv_compact", "specvlm_draft_topk", "specvlm_draft_select", "specvlm_draft_finalize",
+           "specvlm_head_argmax", "specvlm_head_argmax_workspace_bytes"]
 
 
 class SpecvlmError(RuntimeError):
@@ -75,6 +76,10 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.specvlm_draft_select.argtypes = [i32, i32, i32, vp, i64, vp, i32, vp, vp, vp, vp]
     L.specvlm_draft_finalize.restype = i32
     L.specvlm_draft_finalize.argtypes = [i32, i32, i32, vp, vp, vp, i64] + [vp] * 8
+    L.specvlm_head_argmax_workspace_bytes.restype = ctypes.c_size_t
+    L.specvlm_head_argmax_workspace_bytes.argtypes = [i32, i32, i32]
+    L.specvlm_head_argmax.restype = i32
+    L.specvlm_head_argmax.argtypes = [i32] * 5 + [vp, i64, i64, vp, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
     _lib = L
     return L
 
@@ -368,3 +373,28 @@ def specvlm_draft_finalize(cand_score, cand_parent, cand_token, root_token, N_ma
         _ptr(_dev_i32(num_nodes, "num_nodes")), _ptr(err_flag), _stream(stream))
     _check(rc, "specvlm_draft_finalize")
     return parent, tok, node_cand, num_nodes
+
+
+def specvlm_head_argmax_workspace_bytes(B, N_max, V) -> int:
+    return int(lib().specvlm_head_argmax_workspace_bytes(B, N_max, V))
+
+
+def specvlm_head_argmax(hidden, weight, *, num_nodes=None, out=None, max_logit=None, workspace=None, stream=None):
+    """Output head fused with the greedy choice.  hidden [B,N_max,E] bf16, weight [V,E] bf16 ->
+    amax [B,N_max] int32 (and the greatest logit into `max_logit` fp32 [B,N_max] if given)."""
+    B, N_max, E = hidden.shape
+    V = weight.shape[0]
+    if hidden.stride(2) != 1 or weight.stride(1) != 1 or weight.shape[1] != E:
+        raise ValueError("hidden [B,N_max,E] and weight [V,E] need a contiguous last dimension of equal size")
+    if out is None:
+        out = torch.empty((B, N_max), dtype=torch.int32, device=hidden.device)
+    need = specvlm_head_argmax_workspace_bytes(B, N_max, V)
+    if workspace is None:
+        workspace = torch.zeros(need, dtype=torch.uint8, device=hidden.device)   # zero-filled once, as the ABI asks
+    rc = lib().specvlm_head_argmax(
+        _dtype_code(hidden), B, N_max, E, V, _ptr(hidden), hidden.stride(0), hidden.stride(1), _ptr(weight),
+        weight.stride(0), _ptr(_dev_i32(num_nodes, "num_nodes")), _ptr(_dev_i32(out, "out")),
+        _ptr(_dev_f32(max_logit, "max_logit")), _ptr(workspace),
+        ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
+    _check(rc, "specvlm_head_argmax")
+    return out

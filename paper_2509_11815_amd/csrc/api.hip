@@ -173,6 +173,31 @@ int32_t specvlm_kv_compact(const specvlm_attn_desc* desc, int32_t L, void* k_bas
                              static_cast<hipStream_t>(stream));
 }
 
+size_t specvlm_head_argmax_workspace_bytes(int32_t B, int32_t N_max, int32_t V) {
+    if (B < 1 || N_max < 1 || N_max > SPECVLM_MAX_NODES || V < 1 || B > (1 << 20)) return 0;
+    return head_argmax_workspace_bytes(B, N_max, V);
+}
+
+int32_t specvlm_head_argmax(int32_t dtype, int32_t B, int32_t N_max, int32_t E, int32_t V, const void* hidden_dev,
+                            int64_t h_stride_b, int64_t h_stride_n, const void* w_dev, int64_t w_stride_v,
+                            const int32_t* num_nodes_dev, int32_t* amax_dev, float* max_logit_dev,
+                            void* workspace_dev, size_t workspace_bytes, void* stream) {
+    if (dtype != SPECVLM_BF16 && dtype != SPECVLM_F32) return SPECVLM_INVALID_ARG;
+    if (B < 1 || B > (1 << 20) || N_max < 1 || N_max > SPECVLM_MAX_NODES || V < 1 || E < 128 || E % 128)
+        return SPECVLM_INVALID_ARG;
+    if (!hidden_dev || !w_dev || !amax_dev || !workspace_dev) return SPECVLM_INVALID_ARG;
+    if (h_stride_n < E || h_stride_n % 8 || w_stride_v < E || w_stride_v % 8 || w_stride_v > (1 << 24) ||
+        h_stride_n > (1 << 24))
+        return SPECVLM_INVALID_ARG;
+    if (B > 1 && h_stride_b != static_cast<int64_t>(N_max) * h_stride_n) return SPECVLM_INVALID_ARG;
+    if (!aligned16(hidden_dev) || !aligned16(w_dev) || (reinterpret_cast<uintptr_t>(workspace_dev) & 255u))
+        return SPECVLM_INVALID_ARG;
+    if (dtype == SPECVLM_F32) return SPECVLM_UNSUPPORTED;
+    if (workspace_bytes < head_argmax_workspace_bytes(B, N_max, V)) return SPECVLM_WORKSPACE_TOO_SMALL;
+    return launch_head_argmax(B, N_max, E, V, hidden_dev, h_stride_n, w_dev, w_stride_v, num_nodes_dev, amax_dev,
+                              max_logit_dev, workspace_dev, static_cast<hipStream_t>(stream));
+}
+
 int32_t specvlm_draft_topk(int32_t dtype, int32_t B, int32_t W, int32_t V, int32_t K, const void* logits_dev,
                            int64_t stride_b, int64_t stride_w, const float* cum_dev, int64_t cum_stride_b,
                            const int32_t* parent_idx_dev, int64_t parent_stride_b, float* score_out_dev,

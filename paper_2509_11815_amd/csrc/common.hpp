@@ -65,6 +65,11 @@ int32_t launch_kv_compact(const specvlm_attn_desc& d, int32_t L, void* k_base, v
                           int32_t path_cap, const int32_t* accept_len, int32_t* new_prefix_len,
                           int32_t* moved_idx, hipStream_t stream);
 
+size_t head_argmax_workspace_bytes(int32_t B, int32_t N_max, int32_t V);
+int32_t launch_head_argmax(int32_t B, int32_t N_max, int32_t E, int32_t V, const void* hidden,
+                           int64_t h_stride_row, const void* W, int64_t w_stride_v, const int32_t* num_nodes,
+                           int32_t* amax, float* max_logit, void* workspace, hipStream_t stream);
+
 int32_t launch_draft_topk(int32_t dtype, int32_t B, int32_t W, int32_t V, int32_t K, const void* logits,
                           int64_t stride_b, int64_t stride_w, const float* cum, int64_t cum_stride_b,
                           const int32_t* parent_idx, int64_t parent_stride_b, float* score_out,

@@ -1,0 +1,290 @@
+// Output head fused with the greedy choice (SpecVLM Fig. 3: one output head, shared by target
+// and draft; Sec. 4.1: temperature 0): amax[b,i] = argmax_v sum_e hidden[b,i,e] * W[v,e], lowest
+// token on ties, without ever storing the [nodes, vocabulary] logits.
+//
+// The head matrix is read exactly once per block of 64 nodes (262 MB for 32000 x 4096 bf16): the
+// kernel is bound by streaming it from HBM, the products run on the matrix cores.
+//
+//   grid      (vocabulary tiles of 128 rows) x (blocks of 64 node rows).  A workgroup is 8
+//             wavefronts: wavefront (vs, nh) owns the 32 x 32 block (vocabulary rows 32vs..,
+//             nodes 32nh..) of the tile's 128 x 64 logits, 16 accumulator registers
+//   fetch     the contraction runs in chunks of 128 hidden units.  A chunk is 128 rows of W and
+//             64 rows of hidden states, 256 bytes each, brought into a three-slot LDS ring by
+//             direct-to-LDS loads (non-temporal for W, which is used once; the hidden states are
+//             re-read by every workgroup and stay in L2); one load instruction moves four whole
+//             rows, and lands them XOR-swizzled so that the operand reads are conflict-free.
+//             Completion is tracked by hand with s_waitcnt vmcnt; one barrier per chunk
+//             publishes the landed shares and frees the consumed slot
+//   product   logits^T[vocab x node] += W . hidden^T with v_mfma_f32_16x16x32_bf16
+//   epilogue  every lane orders its logits by (greater value, lower token) as one 64-bit key;
+//             keys are maximised across lanes, wavefronts, and -- through a workspace and a
+//             ticket counter -- across the vocabulary tiles by the last workgroup to arrive
+#include <limits.h>
+
+#include "common.hpp"
+
+namespace specvlm {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kHeadThreads = 512;
+constexpr int kVT = 128;                 // vocabulary rows per workgroup
+constexpr int kMB = 64;                  // node rows per workgroup
+constexpr int kKC = 128;                 // hidden units per chunk (256-byte rows in LDS)
+constexpr int kHeadSlots = 3;
+constexpr int kHeadAhead = 2;            // chunks in flight ahead of the one consumed
+constexpr int kWBytes = kVT * kKC * 2;   // 32 KB
+constexpr int kHBytes = kMB * kKC * 2;   // 16 KB
+constexpr int kChunkBytes = kWBytes + kHBytes;
+constexpr int kNIH = (kVT + kMB) / 4 / 8;   // load instructions per wavefront and chunk (4 rows each, 8 wavefronts)
+
+struct HeadParams {
+    const uint16_t* hidden;
+    const uint16_t* W;
+    int64_t h_stride_row;        // elements between consecutive (request, node) rows; rows are b*N_max + i
+    int64_t w_stride_v;
+    int M, E, V, N_max;
+    const int32_t* num_nodes;
+    int32_t* amax;
+    float* max_logit;
+    int32_t* ws_cnt;             // [node blocks] arrival tickets, zero between calls
+    unsigned long long* ws_key;  // [node blocks][vocabulary tiles][64] best keys
+};
+
+__device__ __forceinline__ void head_dma(const void* sbase, uint32_t voff, uint32_t lds_dst, bool stream_once) {
+    if (stream_once)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                     : : "v"(voff), "s"(sbase), "s"(lds_dst) : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     : : "v"(voff), "s"(sbase), "s"(lds_dst) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void head_wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+// (logit, token) as one unsigned key ordered by "greater logit, then lower token"; -0 == +0.
+__device__ __forceinline__ unsigned long long head_key(float v, int idx) {
+    uint32_t u = __float_as_uint(v + 0.0f);
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return (static_cast<unsigned long long>(u) << 32) | (0xFFFFFFFFu - static_cast<uint32_t>(idx));
+}
+
+__device__ __forceinline__ float head_key_value(unsigned long long k) {
+    uint32_t u = static_cast<uint32_t>(k >> 32);
+    u = (u & 0x80000000u) ? (u & 0x7FFFFFFFu) : ~u;
+    return __uint_as_float(u);
+}
+
+__global__ __launch_bounds__(kHeadThreads) void head_argmax_kernel(HeadParams p) {
+    __shared__ __attribute__((aligned(1024))) unsigned char s_ring[kHeadSlots * kChunkBytes];
+    __shared__ unsigned long long s_key[8][kMB];
+    __shared__ int s_flag;
+
+    const int vt = blockIdx.x, mb = blockIdx.y, nvt = gridDim.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int vs = wave & 3, nh = wave >> 2;
+    const int l16 = lane & 15, g = lane >> 4;
+    const int v0 = vt * kVT, m0 = mb * kMB;
+    const int nch = p.E / kKC;
+
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
+    const uint32_t ring_lds = (uint32_t)(uintptr_t)(lds_byte*)s_ring;
+
+    // ---- chunk fetch: load instruction i moves rows 4i .. 4i+3 (lane -> row lane/16, granule lane%16,
+    // fetched from granule position ^ (row % 16)).  W: i = 4*wave + ii (ii < 4); hidden: i = 2*wave + ii
+    // (ii < 2).  Rows past the vocabulary / past the last node row re-read the last real row.
+    const int lrow = lane >> 4, lpos = lane & 15;
+    uint32_t voff_w[4], voff_h[2];
+    const uint16_t* base_w[4];
+    const uint16_t* base_h[2];
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii) {
+        const int r = (4 * wave + ii) * 4 + lrow;                           // row of the tile
+        const int r0 = min(v0 + (4 * wave + ii) * 4, p.V - 1);              // uniform: first row of the group, clamped
+        const int rl = min(v0 + r, p.V - 1) - r0;                           // this lane's row relative to it (>= 0)
+        base_w[ii] = p.W + static_cast<int64_t>(r0) * p.w_stride_v;
+        voff_w[ii] = static_cast<uint32_t>(rl * p.w_stride_v * 2) + (lpos ^ (r & 15)) * 16;
+    }
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii) {
+        const int r = (2 * wave + ii) * 4 + lrow;
+        const int r0 = min(m0 + (2 * wave + ii) * 4, p.M - 1);
+        const int rl = min(m0 + r, p.M - 1) - r0;
+        base_h[ii] = p.hidden + static_cast<int64_t>(r0) * p.h_stride_row;
+        voff_h[ii] = static_cast<uint32_t>(rl * p.h_stride_row * 2) + (lpos ^ (r & 15)) * 16;
+    }
+    auto issue = [&](int j) {
+        const uint32_t dst = ring_lds + (j % kHeadSlots) * kChunkBytes;
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) head_dma(base_w[ii] + j * kKC, voff_w[ii], dst + (4 * wave + ii) * 1024, true);
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+            head_dma(base_h[ii] + j * kKC, voff_h[ii], dst + kWBytes + (2 * wave + ii) * 1024, false);
+    };
+    // waits until at most c chunks' worth of this wavefront's loads are outstanding (c <= kHeadAhead)
+    auto wait_chunks = [&](int c) {
+        if (c >= 2) { head_wait_vmcnt<2 * kNIH>(); return; }
+        if (c == 1) { head_wait_vmcnt<kNIH>(); return; }
+        head_wait_vmcnt<0>();
+    };
+#pragma unroll
+    for (int t = 0; t < kHeadAhead; ++t)
+        if (t < nch) issue(t);
+    wait_chunks(max(0, min(kHeadAhead, nch) - 1));
+    __syncthreads();
+
+    f32x4 acc[2][2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y) acc[x][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int j = 0; j < nch; ++j) {
+        // the slot of chunk j+kHeadAhead held chunk j+kHeadAhead-kHeadSlots <= j-1, consumed before the
+        // barrier that ended the previous iteration
+        if (j + kHeadAhead < nch) issue(j + kHeadAhead);
+        const unsigned char* wt = s_ring + (j % kHeadSlots) * kChunkBytes;
+        const unsigned char* ht = wt + kWBytes;
+        // A: lane (vocab row 32vs + 16x + l16, g) holds hidden units 32c + 8g .. +7 of the chunk;
+        // B: lane (node 32nh + 16y + l16, g) the same units of that node's hidden state
+        bf16x8 wa[2][4], hb[2][4];
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int r = 32 * vs + 16 * x + l16;
+                wa[x][c] = *reinterpret_cast<const bf16x8*>(wt + (r * 16 + ((4 * c + g) ^ (r & 15))) * 16);
+            }
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int r = 32 * nh + 16 * y + l16;
+                hb[y][c] = *reinterpret_cast<const bf16x8*>(ht + (r * 16 + ((4 * c + g) ^ (r & 15))) * 16);
+            }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int y = 0; y < 2; ++y)
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[x][c], hb[y][c], acc[x][y], 0, 0, 0);
+        // this wavefront's reads of the slot have returned and its share of the next chunk has
+        // landed; the barrier extends both to the workgroup
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        wait_chunks(max(0, min(j + kHeadAhead, nch - 1) - (j + 1)));
+        __syncthreads();
+    }
+
+    // ---- epilogue: acc[x][y][i] = logit of token v0 + 32vs + 16x + 4g + i at node m0 + 32nh + 16y + l16
+#pragma unroll
+    for (int y = 0; y < 2; ++y) {
+        unsigned long long best = 0;                       // 0 = no token (a real key is never 0)
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int v = v0 + 32 * vs + 16 * x + 4 * g + i;
+                const unsigned long long k = v < p.V ? head_key(acc[x][y][i], v) : 0ull;
+                best = k > best ? k : best;
+            }
+        unsigned long long o = __shfl_xor(best, 16);
+        best = o > best ? o : best;
+        o = __shfl_xor(best, 32);
+        best = o > best ? o : best;
+        if (g == 0) s_key[vs + 4 * nh][16 * y + l16] = best;        // [vs][nh] x 32 nodes: index node within the half
+    }
+    __syncthreads();
+    if (tid < kMB) {
+        const int half = tid >> 5, within = tid & 31;
+        unsigned long long best = s_key[4 * half][within];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const unsigned long long o = s_key[w + 4 * half][within];
+            best = o > best ? o : best;
+        }
+        // write-through: read by another workgroup in this kernel
+        __hip_atomic_store(p.ws_key + (static_cast<int64_t>(mb) * nvt + vt) * kMB + tid, best, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+    head_wait_vmcnt<0>();                                  // the stores have been acknowledged
+    __syncthreads();
+    if (tid == 0) {
+        const int ticket = __hip_atomic_fetch_add(p.ws_cnt + mb, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = ticket == nvt - 1;
+        if (last) __hip_atomic_store(p.ws_cnt + mb, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_flag = last;
+    }
+    __syncthreads();
+    if (!s_flag) return;
+    // the last workgroup of this node block: node = tid % 64, eight slices of the vocabulary tiles
+    {
+        const int node = tid & 63, slice = tid >> 6;
+        const unsigned long long* src = p.ws_key + static_cast<int64_t>(mb) * nvt * kMB + node;
+        unsigned long long best = 0;
+        for (int t = slice; t < nvt; t += 8) {
+            const unsigned long long o = __hip_atomic_load(src + static_cast<int64_t>(t) * kMB, __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT);
+            best = o > best ? o : best;
+        }
+        s_key[slice][node] = best;
+    }
+    __syncthreads();
+    if (tid < kMB) {
+        unsigned long long best = s_key[0][tid];
+#pragma unroll
+        for (int w = 1; w < 8; ++w) {
+            const unsigned long long o = s_key[w][tid];
+            best = o > best ? o : best;
+        }
+        const int row = m0 + tid;
+        if (row < p.M) {
+            const int b = row / p.N_max, i = row % p.N_max;
+            const int n = p.num_nodes ? p.num_nodes[b] : p.N_max;
+            const bool real = i < n;
+            p.amax[row] = real ? static_cast<int32_t>(0xFFFFFFFFu - static_cast<uint32_t>(best)) : -1;
+            if (p.max_logit) p.max_logit[row] = real ? head_key_value(best) : 0.f;
+        }
+    }
+}
+
+static size_t head_counter_bytes(int mblocks) {
+    return (static_cast<size_t>(mblocks) * sizeof(int32_t) + 255) / 256 * 256;
+}
+
+}  // namespace
+
+size_t head_argmax_workspace_bytes(int32_t B, int32_t N_max, int32_t V) {
+    const int M = B * N_max;
+    const int mblocks = (M + kMB - 1) / kMB, nvt = (V + kVT - 1) / kVT;
+    return head_counter_bytes(mblocks) + static_cast<size_t>(mblocks) * nvt * kMB * sizeof(unsigned long long);
+}
+
+int32_t launch_head_argmax(int32_t B, int32_t N_max, int32_t E, int32_t V, const void* hidden,
+                           int64_t h_stride_row, const void* W, int64_t w_stride_v, const int32_t* num_nodes,
+                           int32_t* amax, float* max_logit, void* workspace, hipStream_t stream) {
+    HeadParams p;
+    p.hidden = static_cast<const uint16_t*>(hidden);
+    p.W = static_cast<const uint16_t*>(W);
+    p.h_stride_row = h_stride_row;
+    p.w_stride_v = w_stride_v;
+    p.M = B * N_max; p.E = E; p.V = V; p.N_max = N_max;
+    p.num_nodes = num_nodes;
+    p.amax = amax;
+    p.max_logit = max_logit;
+    const int mblocks = (p.M + kMB - 1) / kMB, nvt = (V + kVT - 1) / kVT;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    p.ws_cnt = reinterpret_cast<int32_t*>(ws);
+    p.ws_key = reinterpret_cast<unsigned long long*>(ws + head_counter_bytes(mblocks));
+    hipLaunchKernelGGL(head_argmax_kernel, dim3(nvt, mblocks), dim3(kHeadThreads), 0, stream, p);
+    return check_launch();
+}
+
+}  // namespace specvlm
