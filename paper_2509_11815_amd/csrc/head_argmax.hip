@@ -8,8 +8,10 @@
 //   grid      (vocabulary tiles of 128 rows) x (blocks of 64 node rows).  A workgroup is 8
 //             wavefronts: wavefront (vs, nh) owns the 32 x 32 block (vocabulary rows 32vs..,
 //             nodes 32nh..) of the tile's 128 x 64 logits, 16 accumulator registers
-//   fetch     the contraction runs in chunks of 128 hidden units.  A chunk is 128 rows of W and
-//             64 rows of hidden states, 256 bytes each, brought into a three-slot LDS ring by
+//   fetch     the contraction runs in chunks of 128 hidden units, every workgroup starting at a
+//             different chunk (so that the loads in flight spread over all memory channels).  A
+//             chunk is 128 rows of W and 64 rows of hidden states, 256 bytes each, brought into a
+//             three-slot LDS ring by
 //             direct-to-LDS loads (non-temporal for W, which is used once; the hidden states are
 //             re-read by every workgroup and stay in L2); one load instruction moves four whole
 //             rows, and lands them XOR-swizzled so that the operand reads are conflict-free.
@@ -120,13 +122,21 @@ __global__ __launch_bounds__(kHeadThreads) void head_argmax_kernel(HeadParams p)
         base_h[ii] = p.hidden + static_cast<int64_t>(r0) * p.h_stride_row;
         voff_h[ii] = static_cast<uint32_t>(rl * p.h_stride_row * 2) + (lpos ^ (r & 15)) * 16;
     }
+    // The j-th chunk a workgroup takes is chunk (j + rot) mod nch of the hidden dimension: if all
+    // workgroups walked the columns of W in step, every load in flight on the chip would sit at the
+    // same offset inside an 8 KB row, i.e. on a few of the memory channels (measured at 32000 x 4096:
+    // 63 us without the rotation, 55 us with it -- the same as with W repacked into contiguous
+    // 32 KB blocks; multipliers 1, 3, 11, 13 gave 56 us, 7 and 9 gave 58 - 62 us).
+    const int rot = (5 * vt + vt / 8) % nch;
     auto issue = [&](int j) {
         const uint32_t dst = ring_lds + (j % kHeadSlots) * kChunkBytes;
+        int c = j + rot;
+        c = c >= nch ? c - nch : c;
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii) head_dma(base_w[ii] + j * kKC, voff_w[ii], dst + (4 * wave + ii) * 1024, true);
+        for (int ii = 0; ii < 4; ++ii) head_dma(base_w[ii] + c * kKC, voff_w[ii], dst + (4 * wave + ii) * 1024, true);
 #pragma unroll
         for (int ii = 0; ii < 2; ++ii)
-            head_dma(base_h[ii] + j * kKC, voff_h[ii], dst + kWBytes + (2 * wave + ii) * 1024, false);
+            head_dma(base_h[ii] + c * kKC, voff_h[ii], dst + kWBytes + (2 * wave + ii) * 1024, false);
     };
     // waits until at most c chunks' worth of this wavefront's loads are outstanding (c <= kHeadAhead)
     auto wait_chunks = [&](int c) {
