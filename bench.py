@@ -173,6 +173,54 @@ def main():
     run_smp = make_runner(lambda: sv.specvlm_tree_accept_sample(parent, draft_tok, logits, u_accept, u_bonus,
                                                                 temperature=1.0, err_flag=err, out=smp_out))
     ms_smp = timed(run_smp, args.steps, args.warmup)
+    # also outside the step: the draft side's tree growth (Top-K 10, ten nodes expanded per level, `depth`
+    # levels, 60 nodes; the draft model's own forward passes are not part of it) ...
+    K = 10
+    lvl_logits = [torch.randn((B, 1 if d == 0 else K, cfg.V), device=dev, generator=gen).mul_(2).to(torch.bfloat16)
+                  for d in range(cfg.depth)]
+    C = K + (cfg.depth - 1) * K * K
+    c_score = torch.zeros((B, C), dtype=torch.float32, device=dev)
+    c_tok = torch.zeros((B, C), dtype=torch.int32, device=dev)
+    c_par = torch.full((B, C), -1, dtype=torch.int32, device=dev)
+    sel = [(torch.empty((B, K), dtype=torch.int32, device=dev), torch.empty((B, K), dtype=torch.float32, device=dev),
+            torch.empty(B, dtype=torch.int32, device=dev)) for _ in range(cfg.depth)]
+    fin = (torch.empty((B, N), dtype=torch.int32, device=dev), torch.empty((B, N), dtype=torch.int32, device=dev),
+           torch.empty((B, N), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev))
+    root_tok = torch.zeros(B, dtype=torch.int32, device=dev)
+
+    def grow():
+        base, count = 0, 0
+        for d in range(cfg.depth):
+            rows = 1 if d == 0 else K
+            nb = base + count
+            out = dict(score_out=c_score[:, nb:nb + rows * K], token_out=c_tok[:, nb:nb + rows * K],
+                       parent_out=c_par[:, nb:nb + rows * K])
+            if d == 0:
+                sv.specvlm_draft_topk(lvl_logits[d], K, **out)
+            else:
+                sv.specvlm_draft_select(c_score[:, base:base + count], K, index_base=base, sel_out=sel[d][0],
+                                        sel_score_out=sel[d][1], count_out=sel[d][2])
+                sv.specvlm_draft_topk(lvl_logits[d], K, cum=sel[d][1], parent_idx=sel[d][0], **out)
+            base, count = nb, rows * K
+        sv.specvlm_draft_finalize(c_score, c_par, c_tok, root_tok, N, err_flag=err, out=fin)
+
+    ms_grow = timed(make_runner(grow), args.steps, args.warmup)
+    # ... and the output head fused with the greedy choice (it would replace "logits + argmax" of the step when
+    # the caller hands over hidden states instead of logits): hidden 4096 (5120 for the 40-head model), vocab V.
+    # Eight copies of the head matrix are cycled so that none is served from the 256 MB cache.
+    E_h = 128 * H
+    hid = torch.randn((B, N, E_h), device=dev, generator=gen).to(torch.bfloat16)
+    heads = [torch.randn((cfg.V, E_h), device=dev, generator=gen).mul_(2.0 / E_h ** 0.5).to(torch.bfloat16)
+             for _ in range(8)]
+    h_ws = torch.zeros(sv.specvlm_head_argmax_workspace_bytes(B, N, cfg.V), dtype=torch.uint8, device=dev)
+    h_out = torch.empty((B, N), dtype=torch.int32, device=dev)
+
+    def head_calls():
+        for w in heads:
+            sv.specvlm_head_argmax(hid, w, out=h_out, workspace=h_ws)
+
+    ms_head = timed(make_runner(head_calls), max(args.steps // 4, 5), 3) / len(heads)
+    head_bytes = cfg.V * E_h * 2 * ((B * N + 63) // 64)
     assert int(err.item()) == 0, "device error flag set"
 
     kv_bytes_layer = W.kv_bytes_per_layer(cfg)
@@ -202,7 +250,13 @@ def main():
         "verify_steps_per_s": round(1e3 / ms_step, 1),
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "breakdown_ms": {"attention_all_layers": round(ms_attn, 5), "argmax_accept_compact": round(ms_tail, 5)},
-        "outside_the_step_ms": {"tree_accept_sample_T1": round(ms_smp, 5)},
+        "outside_the_step_ms": {"tree_accept_sample_T1": round(ms_smp, 5), "draft_tree_growth": round(ms_grow, 5),
+                                "head_argmax_fused": round(ms_head, 5)},
+        "roofline_head_argmax": {"kernel": "specvlm::head_argmax_kernel", "bound": "hbm",
+                                 "achieved": round(head_bytes / (ms_head * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
+                                 "unit": "GB/s", "frac": round(head_bytes / (ms_head * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                 "algorithmic_bytes_per_launch": head_bytes, "avg_launch_us": round(ms_head * 1e3, 3),
+                                 "traffic": None},
         "roofline": {"kernel": "specvlm::attn_mfma_kernel<128, 4, 2> (the whole specvlm_tree_verify_attn call of one layer)",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),

@@ -23,6 +23,7 @@ namespace {
 
 constexpr int kThreadsDT = 1024;
 constexpr int kWavesDT = kThreadsDT / 64;
+constexpr int kCandCap = 1024;           // Top-K fast path: entries at or above the threshold kept in LDS
 
 template <typename T>
 struct Lane16;
@@ -48,6 +49,12 @@ __device__ __forceinline__ unsigned long long order_key(float v, int idx) {
     uint32_t u = __float_as_uint(v + 0.0f);
     u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
     return (static_cast<unsigned long long>(u) << 32) | (0xFFFFFFFFu - static_cast<uint32_t>(idx));
+}
+
+__device__ __forceinline__ float key_value(unsigned long long k) {     // the logit inside an order_key
+    uint32_t u = static_cast<uint32_t>(k >> 32);
+    u = (u & 0x80000000u) ? (u & 0x7FFFFFFFu) : ~u;
+    return __uint_as_float(u);
 }
 
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x) {
@@ -89,9 +96,10 @@ __device__ __forceinline__ float wg_sum(float x, float* s_red) {
 //   NS > 0: every thread keeps NS vocabulary entries of the row in registers (16-byte loads
 //           when the row is aligned and V a multiple of the vector width, scalar otherwise);
 //   NS == 0: any vocabulary size, every pass re-reads the row (it stays in L2).
-// Passes: maximum, sum of exp(l - max) (log-sum-exp), then K rounds of a workgroup-wide
-// arg-max over (logit, token) keys.  Every thread caches the best key among its entries not
-// yet taken; only the owner of a round's winner rescans its entries.
+// Passes: maximum, sum of exp(l - max) (log-sum-exp), then the K best (logit, token) keys: a
+// threshold from the maxima of 16-lane groups and a rank among the few entries that reach it,
+// or, when too many do, K rounds of a workgroup-wide arg-max (every thread caches the best key
+// among its entries not yet taken; only the owner of a round's winner rescans its entries).
 // ---------------------------------------------------------------------------------------
 template <typename T, int NS>
 __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
@@ -102,6 +110,9 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
     __shared__ float s_red[kWavesDT];
     __shared__ unsigned long long s_key[2][kWavesDT];
     __shared__ int s_taken[SPECVLM_MAX_NODES];         // NS == 0: tokens already taken
+    __shared__ unsigned long long s_grp[64], s_cand[kCandCap];
+    __shared__ unsigned long long s_thr;
+    __shared__ int s_ncand;
 
     const int w = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const int nrows = gridDim.x;
@@ -167,7 +178,91 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
     const int par = parent_idx ? parent_idx[b * parent_stride_b + w] : -1;
     if (tid == 0 && lse_out) lse_out[b * nrows + w] = lse;
 
-    // ---- K rounds of arg-max ---------------------------------------------------------------
+    const int64_t out0 = b * out_stride_b + static_cast<int64_t>(w) * K;
+    auto emit = [&](int k, unsigned long long key) {     // k-th best of the row
+        token_out[out0 + k] = static_cast<int>(0xFFFFFFFFu - static_cast<uint32_t>(key));
+        score_out[out0 + k] = c + (key_value(key) - lse);
+        if (parent_out) parent_out[out0 + k] = par;
+    };
+
+    // ---- fast path: a threshold that at least K entries reach, then a rank among the few that do ----
+    // Every group of 16 lanes reduces the best key of its entries; the K-th best of the 64 group
+    // maxima is a key that K entries of the row reach (the maxima of K different groups), so the
+    // K best entries are among the entries at or above it -- for logits that do not follow the
+    // token order, about 2K of them.  These are collected in LDS and ranked against each other:
+    // an entry beaten by r others is the r-th best.  Keys are distinct, so the result does not
+    // depend on the order in which the entries were collected.  If more than kCandCap entries
+    // reach the threshold (logits sorted along the vocabulary, say) the K rounds below take over.
+    {
+        unsigned long long mine = 0;
+        if constexpr (NS > 0) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const int v = idx_of(s);
+                const unsigned long long k = v < V ? order_key(lv[s], v) : 0ull;
+                mine = k > mine ? k : mine;
+            }
+        } else {
+#pragma unroll 8
+            for (int s = 0; s < ns_mem; ++s) {
+                const int v = tid + kThreadsDT * s;
+                const unsigned long long k = v < V ? order_key(Lane16<T>::one(row + v), v) : 0ull;
+                mine = k > mine ? k : mine;
+            }
+        }
+        unsigned long long grp = mine;
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) {
+            const unsigned long long y = __shfl_xor(grp, off);
+            grp = y > grp ? y : grp;
+        }
+        if (tid == 0) { s_ncand = 0; s_thr = 0; }        // threshold 0: every entry qualifies
+        if ((tid & 15) == 0) s_grp[tid >> 4] = grp;
+        __syncthreads();
+        if (tid < 64) {
+            const unsigned long long g = s_grp[tid];
+            int beaten = 0;
+#pragma unroll 8
+            for (int x = 0; x < 64; ++x) beaten += s_grp[x] > g ? 1 : 0;
+            if (beaten == K - 1 && g != 0) s_thr = g;   // at most one lane (keys are distinct); none when fewer
+        }                                               // than K groups hold an entry: the threshold stays 0
+        __syncthreads();
+        const unsigned long long thr = s_thr;
+        if constexpr (NS > 0) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const int v = idx_of(s);
+                const unsigned long long k = v < V ? order_key(lv[s], v) : 0ull;
+                if (k != 0 && k >= thr) {
+                    const int pos = atomicAdd(&s_ncand, 1);
+                    if (pos < kCandCap) s_cand[pos] = k;
+                }
+            }
+        } else {
+            for (int s = 0; s < ns_mem; ++s) {
+                const int v = tid + kThreadsDT * s;
+                if (v >= V) break;
+                const unsigned long long k = order_key(Lane16<T>::one(row + v), v);
+                if (k >= thr) {
+                    const int pos = atomicAdd(&s_ncand, 1);
+                    if (pos < kCandCap) s_cand[pos] = k;
+                }
+            }
+        }
+        __syncthreads();
+        const int nc = s_ncand;
+        if (nc <= kCandCap) {                           // uniform
+            for (int i = tid; i < nc; i += kThreadsDT) {
+                const unsigned long long k = s_cand[i];
+                int beaten = 0;
+                for (int x = 0; x < nc; ++x) beaten += s_cand[x] > k ? 1 : 0;
+                if (beaten < K) emit(beaten, k);
+            }
+            return;
+        }
+    }
+
+    // ---- K rounds of arg-max (any input) --------------------------------------------------------
     unsigned long long taken = 0;                       // NS > 0: bit s = entry s was taken
     int ntaken = 0;                                     // NS == 0: length of s_taken
     auto local_best = [&]() -> unsigned long long {
@@ -196,7 +291,6 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
         return best;
     };
     unsigned long long mine = local_best();
-    const int64_t out0 = b * out_stride_b + static_cast<int64_t>(w) * K;
     for (int k = 0; k < K; ++k) {
         const unsigned long long wbest = wave_max_u64(mine);
         if ((tid & 63) == 0) s_key[k & 1][tid >> 6] = wbest;
@@ -226,9 +320,7 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
             } else {
                 val = Lane16<T>::one(row + v);
             }
-            token_out[out0 + k] = v;
-            score_out[out0 + k] = c + (val - lse);
-            if (parent_out) parent_out[out0 + k] = par;
+            emit(k, order_key(val, v));
             mine = local_best();
         }
     }
@@ -241,38 +333,51 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
 // s_sc holds the c scores, s_pos (c ints) receives the position of a winner and -1 otherwise.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void rank_winners(const float* s_sc, int* s_pos, int c, int M) {
-    const int tid = threadIdx.x;
-    for (int i = tid; i < c; i += kThreadsDT) {
-        const float si = s_sc[i];
-        int beaten = 0;
-        for (int j = 0; j < c; ++j) {
-            const float sj = s_sc[j];
-            beaten += (sj > si || (sj == si && j < i)) ? 1 : 0;
+    __shared__ int s_wcount[kWavesDT];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c4 = c & ~3;
+    int base = 0;                                          // winners among candidates below this pass
+    for (int i0 = 0; i0 < c; i0 += kThreadsDT) {           // uniform trip count
+        const int i = i0 + tid;
+        bool win = false;
+        if (i < c) {
+            const float si = s_sc[i];
+            int beaten = 0;
+            for (int j = 0; j < c4; j += 4) {              // scores sit 16-byte aligned in LDS
+                const float4 q = *reinterpret_cast<const float4*>(s_sc + j);
+                beaten += (q.x > si || (q.x == si && j < i)) ? 1 : 0;
+                beaten += (q.y > si || (q.y == si && j + 1 < i)) ? 1 : 0;
+                beaten += (q.z > si || (q.z == si && j + 2 < i)) ? 1 : 0;
+                beaten += (q.w > si || (q.w == si && j + 3 < i)) ? 1 : 0;
+            }
+            for (int j = c4; j < c; ++j) {
+                const float sj = s_sc[j];
+                beaten += (sj > si || (sj == si && j < i)) ? 1 : 0;
+            }
+            win = beaten < M;
         }
-        s_pos[i] = beaten < M ? 1 : 0;
-    }
-    __syncthreads();
-    int pos[(SPECVLM_MAX_CANDIDATES + kThreadsDT - 1) / kThreadsDT];
-    int x = 0;
-    for (int i = tid; i < c; i += kThreadsDT, ++x) {
-        int p = -1;
-        if (s_pos[i]) {
-            p = 0;
-            for (int j = 0; j < i; ++j) p += s_pos[j];
+        // position of a winner = winners of lower index: earlier passes, earlier wavefronts, lower lanes
+        const unsigned long long bal = __ballot(win);
+        if (lane == 0) s_wcount[wave] = __popcll(bal);
+        __syncthreads();
+        int before = base, total = 0;
+#pragma unroll
+        for (int x = 0; x < kWavesDT; ++x) {
+            const int n = s_wcount[x];
+            before += x < wave ? n : 0;
+            total += n;
         }
-        pos[x] = p;
+        if (i < c) s_pos[i] = win ? before + __popcll(bal & ((1ull << lane) - 1ull)) : -1;
+        base += total;
+        __syncthreads();                                   // s_wcount is rewritten by the next pass
     }
-    __syncthreads();
-    x = 0;
-    for (int i = tid; i < c; i += kThreadsDT, ++x) s_pos[i] = pos[x];
-    __syncthreads();
 }
 
 __global__ __launch_bounds__(kThreadsDT) void draft_select_kernel(
     int C, int M, const float* __restrict__ score, int64_t score_stride_b, const int32_t* __restrict__ num_cand,
     int index_base, int32_t* __restrict__ sel_out, float* __restrict__ sel_score_out,
     int32_t* __restrict__ count_out) {
-    extern __shared__ unsigned char s_dyn[];
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
     float* s_sc = reinterpret_cast<float*>(s_dyn);
     int* s_pos = reinterpret_cast<int*>(s_dyn) + C;
     const int b = blockIdx.x, tid = threadIdx.x;
@@ -300,7 +405,7 @@ __global__ __launch_bounds__(kThreadsDT) void draft_finalize_kernel(
     const int32_t* __restrict__ cand_token, int64_t cand_stride_b, const int32_t* __restrict__ num_cand,
     const int32_t* __restrict__ root_token, int32_t* __restrict__ parent_out, int32_t* __restrict__ draft_tok_out,
     int32_t* __restrict__ node_cand_out, int32_t* __restrict__ num_nodes_out, int32_t* __restrict__ err_flag) {
-    extern __shared__ unsigned char s_dyn[];
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
     float* s_sc = reinterpret_cast<float*>(s_dyn);
     int* s_pos = reinterpret_cast<int*>(s_dyn) + C;
     const int b = blockIdx.x, tid = threadIdx.x;

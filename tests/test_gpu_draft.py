@@ -81,6 +81,22 @@ def test_topk_ties_signed_zero_inf_and_views(sv, oracle):
     assert torch.all(score_all[:, :20] == 7.0) and torch.all(score_all[:, 50:] == 7.0)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("V,K", [(32000, 10), (40000, 64), (70001, 12), (900, 64)])
+def test_topk_when_the_best_tokens_are_neighbours(sv, oracle, dtype, V, K):
+    """Logits that rise or fall along the vocabulary, or are all equal: far more entries reach the
+    kernel's first threshold than it keeps, so its any-input path has to give the same answer."""
+    from gpu_util import to_dev
+    ramp = np.linspace(-8.0, 8.0, V).astype(np.float32)
+    x = np.stack([ramp, ramp[::-1], np.full(V, 1.5, np.float32), np.round(ramp * 4) / 4])[None]   # [1,4,V]
+    arr = x if dtype == "f32" else W.f32_to_bf16_bits(x)
+    score, token, _ = sv.specvlm_draft_topk(to_dev(arr), K)
+    r_score, r_token, _ = oracle.topk_logprob(arr.reshape(4, V), K)
+    assert np.array_equal(token.cpu().numpy().reshape(4, K), r_token)
+    np.testing.assert_allclose(score.cpu().numpy().reshape(4, K), r_score, rtol=0, atol=SCORE_TOL)
+    assert r_token[2].tolist() == list(range(K))                          # all equal: the lowest tokens
+
+
 @pytest.mark.parametrize("C,M", [(1, 1), (10, 10), (100, 10), (610, 59), (1500, 64), (8192, 40)])
 def test_select_matches_oracle(sv, oracle, C, M):
     from gpu_util import i32
