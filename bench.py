@@ -28,8 +28,13 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/),
 # keyed by workload; None until measured.
 MEASURED_TRAFFIC = {
-    # profiles/attn_mfma_kernel_C3.txt: 29085.6 FETCH_SIZE units x 2.000 KiB + 4841.0 WRITE_SIZE units x 1.000 KiB
-    "C3": {"read_bytes": 59567308, "write_bytes": 4957184, "bytes": 64524492},
+    # profiles/attn_mfma_kernel_C3.txt: 29077.5 FETCH_SIZE units x 2.000 KiB + 4841.0 WRITE_SIZE units x 1.000 KiB
+    "C3": {"read_bytes": 59550720, "write_bytes": 4957184, "bytes": 64507904},
+}
+# the same for the fused output head (profiles/head_argmax_kernel_C3.txt); None until measured
+MEASURED_TRAFFIC_HEAD = {
+    # 130030.2 FETCH_SIZE units x 2.000 KiB + 133.1 WRITE_SIZE units x 1.000 KiB
+    "C3": {"read_bytes": 266301850, "write_bytes": 136294, "bytes": 266438144},
 }
 
 
@@ -43,6 +48,7 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--attn-only", action="store_true", help="profile helper: run only the attention launches")
+    ap.add_argument("--head-only", action="store_true", help="profile helper: run only the fused output-head launches")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profile helper: run plain device copies of a known size (scale for the HBM byte counters)")
     return ap.parse_args()
@@ -152,6 +158,20 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters          # ms per iteration
 
+    if args.head_only:
+        E_h = 128 * H
+        hid = torch.randn((B, N, E_h), device=dev).to(torch.bfloat16)
+        heads = [torch.randn((cfg.V, E_h), device=dev).mul_(2.0 / E_h ** 0.5).to(torch.bfloat16) for _ in range(8)]
+        h_ws = torch.zeros(sv.specvlm_head_argmax_workspace_bytes(B, N, cfg.V), dtype=torch.uint8, device=dev)
+        h_out = torch.empty((B, N), dtype=torch.int32, device=dev)
+
+        def head_calls():
+            for w in heads:
+                sv.specvlm_head_argmax(hid, w, out=h_out, workspace=h_ws)
+
+        ms = timed(make_runner(head_calls), args.steps, args.warmup) / len(heads)
+        print(json.dumps({"head_argmax_ms_per_call": ms}))
+        return
     if args.attn_only:
         run_attn = make_runner(attn_layers)
         ms = timed(run_attn, args.steps, args.warmup)
@@ -256,7 +276,7 @@ def main():
                                  "achieved": round(head_bytes / (ms_head * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
                                  "unit": "GB/s", "frac": round(head_bytes / (ms_head * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                                  "algorithmic_bytes_per_launch": head_bytes, "avg_launch_us": round(ms_head * 1e3, 3),
-                                 "traffic": None},
+                                 "traffic": MEASURED_TRAFFIC_HEAD.get(cfg.name)},
         "roofline": {"kernel": "specvlm::attn_mfma_kernel<128, 4, 2> (the whole specvlm_tree_verify_attn call of one layer)",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
