@@ -347,3 +347,38 @@ def grow_tree(level_logits, root_token, *, K=10, width=10, N_max=60):
     return dict(cand_score=cand_score, cand_parent=cand_parent, cand_token=cand_token, level_sel=level_sel,
                 level_gap=level_gap, parent=parent, draft_tok=tok, node_cand=node_cand, num_nodes=num_nodes,
                 final_gap=gap)
+
+
+# ---- parameter-free visual token compressors (draft side) ------------------------------------------
+
+def visual_pool(x, ratio, num_tokens=None):
+    """x [B,T,E] (uint16 bf16 bits or float32) -> (y [B,ceil(T/ratio),E] float64, out_tokens [B])."""
+    dt = _dtype_code(x)
+    B, T, E = x.shape
+    assert x.strides[2] == x.itemsize
+    st = _estrides(x)
+    nt = None if num_tokens is None else _i32(num_tokens)
+    Tp = (T + ratio - 1) // ratio
+    y = np.zeros((B, Tp, E), dtype=np.float64)
+    out_tokens = np.zeros(B, dtype=np.int32)
+    rc = _load().oracle_visual_pool(ctypes.c_int(dt), ctypes.c_int(B), ctypes.c_int(T), ctypes.c_int(E),
+                                    ctypes.c_int(ratio), _p(x), ctypes.c_int64(st[0]), ctypes.c_int64(st[1]),
+                                    _p(nt), _p(y), _p(out_tokens))
+    if rc:
+        raise ValueError(f"oracle_visual_pool failed with status {rc}")
+    return y, out_tokens
+
+
+def visual_prune(x, keep):
+    """x [B,T,E], keep [B,T_keep] int32 (-1 = padding) -> y [B,T_keep,E] of x's dtype (padding rows zero)."""
+    B, T, E = x.shape
+    assert x.strides[2] == x.itemsize
+    st = _estrides(x)
+    keep = _i32(keep).reshape(B, -1)
+    y = np.zeros((B, keep.shape[1], E), dtype=x.dtype)
+    rc = _load().oracle_visual_prune(ctypes.c_int(x.itemsize), ctypes.c_int(B), ctypes.c_int(T),
+                                     ctypes.c_int(keep.shape[1]), ctypes.c_int(E), _p(x), ctypes.c_int64(st[0]),
+                                     ctypes.c_int64(st[1]), _p(keep), _p(y))
+    if rc:
+        raise ValueError(f"oracle_visual_prune failed with status {rc}")
+    return y

@@ -23,6 +23,8 @@
  *                         the tree region (read-all-then-write)
  *   oracle_head_argmax    the output head applied to the nodes' hidden states, fused
  *                         with the greedy choice (the logits are never stored)
+ *   oracle_visual_pool, oracle_visual_prune
+ *                         the two parameter-free visual token compressors of the draft side
  *   oracle_topk_logprob, oracle_tree_select, oracle_tree_finalize
  *                         the draft side: Top-K expansion of a level, choice of
  *                         the next level's nodes, and the final tree
@@ -39,7 +41,9 @@
  * enumeration of all token sequences (an exhaustively expanded tree must hold
  * exactly the most probable sequences); for the fused head, numpy's float64 matmul
  * + argmax, one-hot head rows, integer-valued inputs whose fp32 logits are exact
- * (then it must agree with oracle_node_argmax on the stored logits) and duplicate rows.
+ * (then it must agree with oracle_node_argmax on the stored logits) and duplicate rows;
+ * for the compressors, numpy's reshape-mean and fancy indexing, ratio 1 = identity, constant
+ * inputs, and the mean's linearity.
  *
  * Only tests/, the smoke check and the benchmark's cpu_baseline leg may call
  * this file.  It shares no code with the HIP library.
@@ -549,6 +553,56 @@ int oracle_tree_finalize(int B, int C, int N_max, const float *cand_score, const
     }
     free(sel); free(node_of);
     return rc;
+}
+
+/*
+ * ---- parameter-free visual token compressors (Sec. 3.3: "Pruning drops tokens at random; Pooling
+ * [is a] vanilla" operator; Table 4 uses ratios 2x .. 30x) ------------------------------------------
+ * They shorten the visual prefix the DRAFT reads (the target keeps the full sequence, which is what
+ * keeps decoding lossless).  The paper fixes neither the pooling window nor what happens to a ragged
+ * tail; the reading here: average pooling along the token sequence with window = stride = ratio, the
+ * last window shorter when the length is not a multiple (mean over the tokens it has):
+ *     y[b,j,:] = mean_{t = j*ratio .. min((j+1)*ratio, T_b) - 1} x[b,t,:],   j < ceil(T_b / ratio)
+ * and pruning keeps the tokens whose indices the caller drew (any order, repeats allowed):
+ *     y[b,j,:] = x[b, keep[b,j], :]            (keep[b,j] = -1: row j is padding and left untouched)
+ * Output in double (pool) / bit copies (prune).  out_tokens[b] = ceil(T_b / ratio).
+ */
+int oracle_visual_pool(int dtype, int B, int T, int E, int ratio, const void *x, int64_t x_stride_b,
+                       int64_t x_stride_t, const int32_t *num_tokens, double *y, int32_t *out_tokens)
+{
+    if (ratio < 1) return 1;
+    const int Tp = (T + ratio - 1) / ratio;
+    for (int b = 0; b < B; ++b) {
+        const int tb = num_tokens ? num_tokens[b] : T;
+        if (tb < 0 || tb > T) return 1;
+        const int nb = (tb + ratio - 1) / ratio;
+        if (out_tokens) out_tokens[b] = nb;
+        for (int j = 0; j < nb; ++j) {
+            const int t0 = j * ratio, t1 = (j + 1) * ratio < tb ? (j + 1) * ratio : tb;
+            for (int e = 0; e < E; ++e) {
+                double acc = 0.0;
+                for (int t = t0; t < t1; ++t)
+                    acc += elem_as_double(x, dtype, (int64_t)b * x_stride_b + (int64_t)t * x_stride_t + e);
+                y[((int64_t)b * Tp + j) * E + e] = acc / (double)(t1 - t0);
+            }
+        }
+    }
+    return 0;
+}
+
+int oracle_visual_prune(int elem_bytes, int B, int T, int T_keep, int E, const void *x, int64_t x_stride_b,
+                        int64_t x_stride_t, const int32_t *keep, void *y)
+{
+    for (int b = 0; b < B; ++b)
+        for (int j = 0; j < T_keep; ++j) {
+            const int t = keep[(int64_t)b * T_keep + j];
+            if (t == -1) continue;
+            if (t < 0 || t >= T) return 1;
+            memcpy((char *)y + ((int64_t)b * T_keep + j) * E * elem_bytes,
+                   (const char *)x + ((int64_t)b * x_stride_b + (int64_t)t * x_stride_t) * elem_bytes,
+                   (size_t)E * elem_bytes);
+        }
+    return 0;
 }
 
 /*
