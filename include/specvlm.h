@@ -225,6 +225,36 @@ int32_t specvlm_kv_compact(const specvlm_attn_desc *desc, int32_t L,
                            int32_t *new_prefix_len_dev, int32_t *moved_idx_dev, void *stream);
 
 /*
+ * Parameter-free visual token compressors (Sec. 3.3: "Pruning drops tokens at random", pooling is a
+ * vanilla operator; Table 4: ratios 2x .. 30x).  They shorten the visual prefix the DRAFT reads;
+ * the target keeps the full sequence (that is what keeps decoding lossless).  The paper fixes
+ * neither the pooling window nor the treatment of a ragged tail; here: average pooling along the
+ * token sequence, window = stride = ratio, the last window shorter when the length is not a multiple:
+ *     y[b,j,:] = mean_{t = j*ratio .. min((j+1)*ratio, T_b) - 1} x[b,t,:]   for j < ceil(T_b / ratio)
+ * (fp32 sum in token order, one multiplication by 1/count, rounded to dtype), T_b = num_tokens[b]
+ * (NULL: T); rows j >= ceil(T_b / ratio) of y are left untouched; out_tokens[b] = ceil(T_b / ratio).
+ * num_tokens[b] outside [0, T] is clamped and sets SPECVLM_ERR_BAD_LENGTH.
+ *   x_dev  device, dtype, element (b,t,e) at b*x_stride_b + t*x_stride_t + e; E*sizeof(dtype) a
+ *          multiple of 16, rows 16-byte aligned
+ *   y_dev  device, dtype, [B, ceil(T/ratio), E] via y_stride_b / y_stride_t, same alignment
+ */
+int32_t specvlm_visual_pool(int32_t dtype, int32_t B, int32_t T, int32_t E, int32_t ratio,
+                            const void *x_dev, int64_t x_stride_b, int64_t x_stride_t,
+                            const int32_t *num_tokens_dev, void *y_dev, int64_t y_stride_b,
+                            int64_t y_stride_t, int32_t *out_tokens_dev, int32_t *err_flag_dev,
+                            void *stream);
+
+/*
+ * Pruning: y[b,j,:] = x[b, keep[b,j], :] (bit copy) for the T_keep token indices the caller drew
+ * (any order, repeats allowed; keep[b,j] == -1 marks padding and leaves row j untouched; an index
+ * outside [0, T) leaves the row untouched and sets SPECVLM_ERR_BAD_LENGTH).  Layout rules as above.
+ */
+int32_t specvlm_visual_prune(int32_t dtype, int32_t B, int32_t T, int32_t T_keep, int32_t E,
+                             const void *x_dev, int64_t x_stride_b, int64_t x_stride_t,
+                             const int32_t *keep_dev, void *y_dev, int64_t y_stride_b,
+                             int64_t y_stride_t, int32_t *err_flag_dev, void *stream);
+
+/*
  * Output head fused with the greedy choice (Fig. 3: target and draft share one output head;
  * Sec. 4.1: temperature 0).  Replaces "project to logits, store them, specvlm_node_argmax":
  *     logit[b,i,v] = sum_e hidden[b,i,e] * W[v,e]          (bf16 products, fp32 accumulation)

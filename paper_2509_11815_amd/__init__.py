@@ -22,4 +22,6 @@ from .binding import (  # noqa: F401
     specvlm_tree_verify_attn_num_splits,
     specvlm_tree_verify_attn_workspace_bytes,
     specvlm_version,
+    specvlm_visual_pool,
+    specvlm_visual_prune,
 )

@@ -21,7 +21,8 @@ EXPORTS = ["specvlm_version", "specvlm_last_hip_error", "specvlm_tree_verify_att
            "specvlm_tree_verify_attn_num_splits",
            "specvlm_tree_verify_attn", "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_tree_accept_sample",
            "specvlm_kv_compact", "specvlm_draft_topk", "specvlm_draft_select", "specvlm_draft_finalize",
-           "specvlm_head_argmax", "specvlm_head_argmax_workspace_bytes"]
+           "specvlm_head_argmax", "specvlm_head_argmax_workspace_bytes",
+           "specvlm_visual_pool", "specvlm_visual_prune"]
 
 
 class SpecvlmError(RuntimeError):
@@ -80,6 +81,10 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.specvlm_head_argmax_workspace_bytes.argtypes = [i32, i32, i32]
     L.specvlm_head_argmax.restype = i32
     L.specvlm_head_argmax.argtypes = [i32] * 5 + [vp, i64, i64, vp, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.specvlm_visual_pool.restype = i32
+    L.specvlm_visual_pool.argtypes = [i32] * 5 + [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp]
+    L.specvlm_visual_prune.restype = i32
+    L.specvlm_visual_prune.argtypes = [i32] * 5 + [vp, i64, i64, vp, vp, i64, i64, vp, vp]
     _lib = L
     return L
 
@@ -397,4 +402,37 @@ def specvlm_head_argmax(hidden, weight, *, num_nodes=None, out=None, max_logit=N
         _ptr(_dev_f32(max_logit, "max_logit")), _ptr(workspace),
         ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream))
     _check(rc, "specvlm_head_argmax")
+    return out
+
+
+def specvlm_visual_pool(x, ratio, *, num_tokens=None, out=None, out_tokens=None, err_flag=None, stream=None):
+    """Average pooling along the token sequence (window = stride = ratio, ragged last window).
+    x [B,T,E] -> (y [B,ceil(T/ratio),E], out_tokens [B] int32)."""
+    B, T, E = x.shape
+    Tp = (T + ratio - 1) // ratio if ratio > 0 else T      # (the library rejects ratio < 1)
+    if out is None:
+        out = torch.zeros((B, Tp, E), dtype=x.dtype, device=x.device)
+    if out_tokens is None:
+        out_tokens = torch.empty(B, dtype=torch.int32, device=x.device)
+    if x.stride(2) != 1 or out.stride(2) != 1:
+        raise ValueError("feature dimension must be contiguous")
+    rc = lib().specvlm_visual_pool(_dtype_code(x), B, T, E, ratio, _ptr(x), x.stride(0), x.stride(1),
+                                   _ptr(_dev_i32(num_tokens, "num_tokens")), _ptr(out), out.stride(0), out.stride(1),
+                                   _ptr(_dev_i32(out_tokens, "out_tokens")), _ptr(err_flag), _stream(stream))
+    _check(rc, "specvlm_visual_pool")
+    return out, out_tokens
+
+
+def specvlm_visual_prune(x, keep, *, out=None, err_flag=None, stream=None):
+    """Pruning as a gather: x [B,T,E], keep [B,T_keep] int32 (-1 = padding) -> y [B,T_keep,E]."""
+    B, T, E = x.shape
+    T_keep = keep.shape[1]
+    if out is None:
+        out = torch.zeros((B, T_keep, E), dtype=x.dtype, device=x.device)
+    if x.stride(2) != 1 or out.stride(2) != 1:
+        raise ValueError("feature dimension must be contiguous")
+    rc = lib().specvlm_visual_prune(_dtype_code(x), B, T, T_keep, E, _ptr(x), x.stride(0), x.stride(1),
+                                    _ptr(_dev_i32(keep, "keep")), _ptr(out), out.stride(0), out.stride(1),
+                                    _ptr(err_flag), _stream(stream))
+    _check(rc, "specvlm_visual_prune")
     return out

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libspecvlm.so")
-SOURCES = ["api.hip", "sample_kernels.hip", "accept_sample.hip", "draft_tree.hip", "head_argmax.hip", "attn_valu.hip", "attn_mfma.hip"]
+SOURCES = ["api.hip", "sample_kernels.hip", "accept_sample.hip", "draft_tree.hip", "head_argmax.hip", "compress.hip", "attn_valu.hip", "attn_mfma.hip"]
 
 
 def hipcc_command(out: str = LIB) -> list[str]:

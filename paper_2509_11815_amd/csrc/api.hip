@@ -173,6 +173,35 @@ int32_t specvlm_kv_compact(const specvlm_attn_desc* desc, int32_t L, void* k_bas
                              static_cast<hipStream_t>(stream));
 }
 
+static bool rows_ok(int32_t dtype, int32_t E, const void* p, int64_t sb, int64_t st) {
+    const int vec = dtype == SPECVLM_BF16 ? 8 : 4;
+    return p && aligned16(p) && E >= vec && E % vec == 0 && st >= E && st % vec == 0 && sb >= 0 && sb % vec == 0;
+}
+
+int32_t specvlm_visual_pool(int32_t dtype, int32_t B, int32_t T, int32_t E, int32_t ratio, const void* x_dev,
+                            int64_t x_stride_b, int64_t x_stride_t, const int32_t* num_tokens_dev, void* y_dev,
+                            int64_t y_stride_b, int64_t y_stride_t, int32_t* out_tokens_dev, int32_t* err_flag_dev,
+                            void* stream) {
+    if (dtype != SPECVLM_BF16 && dtype != SPECVLM_F32) return SPECVLM_INVALID_ARG;
+    if (B < 1 || B > 65535 || T < 1 || ratio < 1) return SPECVLM_INVALID_ARG;
+    if (!rows_ok(dtype, E, x_dev, x_stride_b, x_stride_t) || !rows_ok(dtype, E, y_dev, y_stride_b, y_stride_t))
+        return SPECVLM_INVALID_ARG;
+    return launch_visual_pool(dtype, B, T, E, ratio, x_dev, x_stride_b, x_stride_t, num_tokens_dev, y_dev,
+                              y_stride_b, y_stride_t, out_tokens_dev, err_flag_dev, static_cast<hipStream_t>(stream));
+}
+
+int32_t specvlm_visual_prune(int32_t dtype, int32_t B, int32_t T, int32_t T_keep, int32_t E, const void* x_dev,
+                             int64_t x_stride_b, int64_t x_stride_t, const int32_t* keep_dev, void* y_dev,
+                             int64_t y_stride_b, int64_t y_stride_t, int32_t* err_flag_dev, void* stream) {
+    if (dtype != SPECVLM_BF16 && dtype != SPECVLM_F32) return SPECVLM_INVALID_ARG;
+    if (B < 1 || B > 65535 || T < 1 || T_keep < 1 || !keep_dev) return SPECVLM_INVALID_ARG;
+    if (!rows_ok(dtype, E, x_dev, x_stride_b, x_stride_t) || !rows_ok(dtype, E, y_dev, y_stride_b, y_stride_t))
+        return SPECVLM_INVALID_ARG;
+    return launch_visual_prune(dtype == SPECVLM_BF16 ? 2 : 4, B, T, T_keep, E, x_dev, x_stride_b, x_stride_t,
+                               keep_dev, y_dev, y_stride_b, y_stride_t, err_flag_dev,
+                               static_cast<hipStream_t>(stream));
+}
+
 size_t specvlm_head_argmax_workspace_bytes(int32_t B, int32_t N_max, int32_t V) {
     if (B < 1 || N_max < 1 || N_max > SPECVLM_MAX_NODES || V < 1 || B > (1 << 20)) return 0;
     return head_argmax_workspace_bytes(B, N_max, V);

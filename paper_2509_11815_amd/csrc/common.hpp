@@ -65,6 +65,13 @@ int32_t launch_kv_compact(const specvlm_attn_desc& d, int32_t L, void* k_base, v
                           int32_t path_cap, const int32_t* accept_len, int32_t* new_prefix_len,
                           int32_t* moved_idx, hipStream_t stream);
 
+int32_t launch_visual_pool(int32_t dtype, int32_t B, int32_t T, int32_t E, int32_t ratio, const void* x,
+                           int64_t x_sb, int64_t x_st, const int32_t* num_tokens, void* y, int64_t y_sb,
+                           int64_t y_st, int32_t* out_tokens, int32_t* err_flag, hipStream_t stream);
+int32_t launch_visual_prune(int32_t elem_bytes, int32_t B, int32_t T, int32_t T_keep, int32_t E, const void* x,
+                            int64_t x_sb, int64_t x_st, const int32_t* keep, void* y, int64_t y_sb, int64_t y_st,
+                            int32_t* err_flag, hipStream_t stream);
+
 size_t head_argmax_workspace_bytes(int32_t B, int32_t N_max, int32_t V);
 int32_t launch_head_argmax(int32_t B, int32_t N_max, int32_t E, int32_t V, const void* hidden,
                            int64_t h_stride_row, const void* W, int64_t w_stride_v, const int32_t* num_nodes,
