@@ -50,7 +50,7 @@ using namespace specvlm;
 
 extern "C" {
 
-int32_t specvlm_version(void) { return 100; }
+int32_t specvlm_version(void) { return 200; }
 
 int32_t specvlm_last_hip_error(void) { return g_last_hip_error; }
 
