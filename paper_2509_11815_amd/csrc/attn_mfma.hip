@@ -37,8 +37,9 @@
 //   merge     the streams of a workgroup are merged through LDS (one round, the rings are
 //             free by then; 4 wavefronts each end up owning 16 query rows); the
 //             workgroup's partial goes, as bf16, to a lane-major
-//             workspace with write-through stores, and the last workgroup of a
-//             (request, head) to arrive -- found with a ticket counter -- merges the splits
+//             workspace with write-through stores, and for every query block the last
+//             split to arrive -- found with a ticket counter per (request, head, query
+//             block) -- merges the splits, adding a split up while the next ones still load
 #include "common.hpp"
 
 namespace specvlm {
@@ -72,7 +73,7 @@ struct MfmaParams {
     int64_t q_sb, q_sn, q_sh, o_sb, o_sn, o_sh;
     const int32_t *prefix_len, *num_nodes, *parent;
     int32_t* err_flag;
-    int32_t* ws_cnt;            // [B*H_q] arrival tickets, zero between calls
+    int32_t* ws_cnt;            // [B*H_q][4 query blocks] arrival tickets, zero between calls
     float* ws_acc;              // [B*H_q*num_splits][4 qb][NT/2][64 lanes] 16-byte vectors of packed bf16
     float* ws_ml;               // [B*H_q*num_splits][64 q][2] (max, sum)
 };
@@ -114,6 +115,19 @@ __device__ __forceinline__ void dma4(const void* gsrc, uint32_t lds_dst) {
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+// The same for a count that is a constant only after loop unrolling (an even number up to 30).
+__device__ __forceinline__ void wait_vmcnt_unrolled(int n) {
+    switch (n) {
+#define SPECVLM_WAIT_CASE(N) case N: wait_vmcnt<N>(); break;
+        SPECVLM_WAIT_CASE(0) SPECVLM_WAIT_CASE(2) SPECVLM_WAIT_CASE(4) SPECVLM_WAIT_CASE(6) SPECVLM_WAIT_CASE(8)
+        SPECVLM_WAIT_CASE(10) SPECVLM_WAIT_CASE(12) SPECVLM_WAIT_CASE(14) SPECVLM_WAIT_CASE(16) SPECVLM_WAIT_CASE(18)
+        SPECVLM_WAIT_CASE(20) SPECVLM_WAIT_CASE(22) SPECVLM_WAIT_CASE(24) SPECVLM_WAIT_CASE(26) SPECVLM_WAIT_CASE(28)
+        SPECVLM_WAIT_CASE(30)
+#undef SPECVLM_WAIT_CASE
+        default: wait_vmcnt<0>(); break;
+    }
 }
 
 // Write-through (device-coherent) 16-byte store for data that another workgroup, possibly
@@ -171,7 +185,6 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     __shared__ float s_m[kStreams][kQRows];
     __shared__ float s_l[kStreams][kQRows];
     __shared__ int s_par[SPECVLM_MAX_NODES];
-    __shared__ int s_flag;
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of work
     // items so that all splits of a (request, head) share one L2 (their partials meet there).
@@ -539,12 +552,16 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         return;
     }
     // ---- split partials: write-through stores, ticket, the last arrival merges ------------------
+    // From here on every owner wavefront goes its own way (no workgroup barrier): it stores its
+    // query block's partial, draws a ticket of its (request, head, query block), and the wavefront
+    // that finds all other splits' tickets drawn merges that block.
+    if (!wave_active) return;
     const int64_t part0 = static_cast<int64_t>(bh) * p.num_splits;
     // Partials are kept in bf16 (halves the bytes one compute unit must pull for the merge);
     // the same rounding is applied to the final output anyway.  Dword i*NT/2 + t/2 of a lane
     // packs out[t][i], out[t+1][i].
     constexpr int PV4 = NT / 2;                        // 16-byte vectors per lane per partial
-    if (wave_active) {
+    {
         u32x4* dst = reinterpret_cast<u32x4*>(p.ws_acc) + ((part0 + split) * 4 + q4) * PV4 * 64;
         uint32_t w[4][NT / 2];
 #pragma unroll
@@ -565,91 +582,103 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
             __hip_atomic_store(reinterpret_cast<uint32_t*>(ml + 1), __float_as_uint(Lq), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    wait_vmcnt<0>();                                   // the write-through stores have been acknowledged
-    __syncthreads();
-    if (tid == 0) {
-        const int ticket = __hip_atomic_fetch_add(p.ws_cnt + bh, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int last = ticket == p.num_splits - 1;
+    wait_vmcnt<0>();                                   // this wavefront's write-through stores have been acknowledged
+    int is_last = 0;
+    if (lane == 0) {
+        int32_t* cnt = p.ws_cnt + static_cast<int64_t>(bh) * 4 + q4;
+        const int ticket = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = ticket == p.num_splits - 1;
         // every other split has already drawn its ticket: leave the counter zero for the next call
-        if (last) __hip_atomic_store(p.ws_cnt + bh, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_flag = last;
+        if (is_last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __syncthreads();
-    if (!s_flag || !wave_active) return;
+    if (!__builtin_amdgcn_readfirstlane(is_last)) return;
     // The partials are read with device-coherent loads (the encoding of an agent-scope atomic load:
     // they never return what this compute unit or its L2 still holds of the workspace from
     // earlier calls), issued after the ticket was seen; this is cheaper than an acquire fence,
-    // which would also invalidate the L2.  The compiler does not track these loads: load_batch
-    // waits for them itself and passes the registers through an empty asm, so that no use can
-    // be scheduled before the wait.
-    auto ld16 = [](const u32x4* a) {
-        u32x4 v;
-        asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(a) : "memory");
-        return v;
+    // which would also invalidate the L2.  The compiler does not track these loads: they are
+    // waited for by hand -- loads complete in order, so the reference maxima (requested first) can
+    // be reduced and split u can be added up while the partials of the splits after it are still
+    // on their way -- and every register passes through an empty asm after its wait, so that no
+    // use can be scheduled before it.
+    // Addresses are a uniform base (the split) plus a lane offset that never changes, so the 40
+    // loads of a batch tie up no address registers.
+    const uint32_t voff_part = lane * 16, voff_ml = qi * 8;
+    const unsigned char* acc_base = reinterpret_cast<const unsigned char*>(p.ws_acc) + (part0 * 4 + q4) * PV4 * 1024;
+    const unsigned char* ml_base = reinterpret_cast<const unsigned char*>(p.ws_ml) + part0 * kQRows * 8;
+    auto ld_part = [&](int se, int v) {                 // 16-byte vector v of split se's partial of this query block
+        u32x4 r;
+        const unsigned char* sb = acc_base + static_cast<int64_t>(se) * (4 * PV4 * 1024) + v * 1024;
+        asm volatile("global_load_dwordx4 %0, %1, %2 sc1" : "=v"(r) : "v"(voff_part), "s"(sb) : "memory");
+        return r;
     };
-    auto ld8 = [](const float2* a) {
-        f32x2 v;
-        asm volatile("global_load_dwordx2 %0, %1, off sc1" : "=v"(v) : "v"(a) : "memory");
-        return v;
+    auto ld_ml = [&](int se) {                          // (reference maximum, sum) of split se for this lane's query row
+        f32x2 r;
+        const unsigned char* sb = ml_base + static_cast<int64_t>(se) * (kQRows * 8);
+        asm volatile("global_load_dwordx2 %0, %1, %2 sc1" : "=v"(r) : "v"(voff_ml), "s"(sb) : "memory");
+        return r;
     };
-    const float2* mlp = reinterpret_cast<const float2*>(p.ws_ml) + part0 * kQRows + qi;
-    const u32x4* accp = reinterpret_cast<const u32x4*>(p.ws_acc) + (part0 * 4 + q4) * PV4 * 64 + lane;
     const int last = p.num_splits - 1;
-    // Splits are taken 8 at a time, every load of a batch issued before its first use; indices
-    // past the last split are clamped and given weight zero, so there is no branch.  The first
-    // batch is requested together with the reference maxima it will be weighted by.
-    u32x4 part[8][PV4];
-    f32x2 ml[8];
-    auto load_batch = [&](int s0) {
+    float Mall = -INFINITY, Lall = 0.f;
+    auto add_split = [&](const u32x4 (&pv)[PV4], float w) {     // out += w * partial
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int64_t se = min(s0 + u, last);
-            ml[u] = ld8(mlp + se * kQRows);
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int v = 0; v < PV4; ++v) part[u][v] = ld16(accp + (se * 4 * PV4 + v) * 64);
-        }
-        wait_vmcnt<0>();
+            for (int t = 0; t < NT; t += 2) {
+                const int dw = i * (NT / 2) + t / 2;
+                const uint32_t x = pv[dw >> 2][dw & 3];
+                out[t][i] = fmaf(__uint_as_float(x << 16), w, out[t][i]);
+                out[t + 1][i] = fmaf(__uint_as_float(x & 0xFFFF0000u), w, out[t + 1][i]);
+            }
+    };
+    if (p.num_splits <= 8) {                           // uniform; what the library chooses by itself
+        // One batch of 8 + 8*PV4 loads: maxima and sums first, then the partials in split order;
+        // indices past the last split are clamped and given weight zero, so there is no branch.
+        u32x4 part[8][PV4];
+        f32x2 ml[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) ml[u] = ld_ml(min(u, last));
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int v = 0; v < PV4; ++v) part[u][v] = ld_part(min(u, last), v);
+        wait_vmcnt<8 * PV4>();                         // the maxima and sums have landed
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             asm volatile("" : "+v"(ml[u]));
+            Mall = fmaxf(Mall, ml[u][0]);
+        }
+        const float m_safe = Mall == -INFINITY ? 0.f : Mall;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) out[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            wait_vmcnt_unrolled((7 - u) * PV4);        // the partial of split u has landed
 #pragma unroll
             for (int v = 0; v < PV4; ++v) asm volatile("" : "+v"(part[u][v]));
-        }
-    };
-    load_batch(0);
-    float Mall = -INFINITY;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) Mall = fmaxf(Mall, ml[u][0]);
-    for (int s0 = 8; s0 < p.num_splits; s0 += 8) {
-        float mv[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            f32x2 t2 = ld8(mlp + min(s0 + u, last) * kQRows);
-            asm volatile("s_waitcnt vmcnt(0)" : "+v"(t2) : : "memory");
-            mv[u] = t2[0];
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) Mall = fmaxf(Mall, mv[u]);
-    }
-    const float m_safe = Mall == -INFINITY ? 0.f : Mall;
-    float Lall = 0.f;
-#pragma unroll
-    for (int t = 0; t < NT; ++t) out[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int s0 = 0; s0 < p.num_splits; s0 += 8) {
-        if (s0 > 0) load_batch(s0);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const float w = s0 + u <= last ? fast_exp2((ml[u][0] - m_safe) * c2) : 0.f;
+            const float w = u <= last ? fast_exp2((ml[u][0] - m_safe) * c2) : 0.f;
             Lall += ml[u][1] * w;
+            add_split(part[u], w);
+        }
+    } else {                                           // a caller's larger split count: one split at a time
+        for (int se = 0; se <= last; ++se) {
+            f32x2 t2 = ld_ml(se);
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(t2) : : "memory");
+            Mall = fmaxf(Mall, t2[0]);
+        }
+        const float m_safe = Mall == -INFINITY ? 0.f : Mall;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+        for (int t = 0; t < NT; ++t) out[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int se = 0; se <= last; ++se) {
+            f32x2 t2 = ld_ml(se);
+            u32x4 pv[PV4];
 #pragma unroll
-                for (int t = 0; t < NT; t += 2) {
-                    const int dw = i * (NT / 2) + t / 2;
-                    const uint32_t x = part[u][dw >> 2][dw & 3];
-                    out[t][i] = fmaf(__uint_as_float(x << 16), w, out[t][i]);
-                    out[t + 1][i] = fmaf(__uint_as_float(x & 0xFFFF0000u), w, out[t + 1][i]);
-                }
+            for (int v = 0; v < PV4; ++v) pv[v] = ld_part(se, v);
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(t2) : : "memory");
+#pragma unroll
+            for (int v = 0; v < PV4; ++v) asm volatile("" : "+v"(pv[v]));
+            const float w = fast_exp2((t2[0] - m_safe) * c2);
+            Lall += t2[1] * w;
+            add_split(pv, w);
         }
     }
     store_rows<NT>(p, out, Mall, Lall, b, h, qi, g, n);
@@ -690,7 +719,7 @@ int32_t attn_mfma_pick_splits(const specvlm_attn_desc& d) {
 }
 
 static size_t counter_bytes(const specvlm_attn_desc& d) {
-    const size_t raw = static_cast<size_t>(d.B) * d.H_q * sizeof(int32_t);
+    const size_t raw = static_cast<size_t>(d.B) * d.H_q * 4 * sizeof(int32_t);
     return (raw + kCounterAlign - 1) / kCounterAlign * kCounterAlign;
 }
 

@@ -68,7 +68,7 @@ def test_small_cases_ragged_gqa(sv, oracle, D, dtype):
     check(case, *run_both(sv, oracle, case, scale=0.11), f"small D={D} {dtype}")
 
 
-@pytest.mark.parametrize("num_splits", [1, 2, 3, 5, 16])
+@pytest.mark.parametrize("num_splits", [1, 2, 3, 5, 8, 9, 16])
 def test_bf16_split_counts_span_tiles_and_tail(sv, oracle, num_splits):
     """S = 333+60 keys: 25 sixteen-key blocks, a ragged last block, an odd tile count;
     more splits than some ranges have blocks."""
