@@ -161,3 +161,44 @@ def test_error_reporting(sv):
     with pytest.raises(sv.SpecvlmError, match="WORKSPACE_TOO_SMALL"):
         sv.specvlm_tree_verify_attn(q, k, v, P, i32(case["parent"]), num_splits=4,
                                     workspace=torch.zeros(256, dtype=torch.uint8, device="cuda"))
+
+
+def test_one_workspace_across_shapes_and_graph_replays(sv, oracle):
+    """The workspace is zero-filled once and then shared by calls of different shapes (every call
+    leaves its counters zero); a captured call replays to the eager result, with eager work and
+    synchronisations between the replays."""
+    from gpu_util import random_case, i32, to_dev, to_host_f64, assert_attn_close
+    big = random_case(81, "bf16", B=2, Hq=4, Hkv=4, D=128, N_max=60, P_list=[700, 90])
+    small = random_case(82, "bf16", B=1, Hq=2, Hkv=1, D=64, N_max=17, P_list=[130])
+    refs = {id(c): oracle.tree_attn(c["q"], c["k"], c["v"], c["prefix_len"], c["parent"])[0] for c in (big, small)}
+    dev = {id(c): tuple(to_dev(c[x]) for x in ("q", "k", "v")) + (i32(c["prefix_len"]), i32(c["parent"]))
+           for c in (big, small)}
+    ws = torch.zeros(1 << 22, dtype=torch.uint8, device="cuda")
+    for rnd in range(3):
+        for c, splits in ((big, 5), (small, 3), (big, 2), (small, 7)):
+            q, k, v, P, par = dev[id(c)]
+            out = sv.specvlm_tree_verify_attn(q, k, v, P, par, workspace=ws, num_splits=splits)
+            assert_attn_close(to_host_f64(out), refs[id(c)], "bf16", f"round {rnd} splits {splits}")
+    # graph capture of one call; the inputs are refreshed in place between replays
+    q, k, v, P, par = dev[id(big)]
+    out = torch.zeros_like(q)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sv.specvlm_tree_verify_attn(q, k, v, P, par, out=out, workspace=ws, num_splits=4)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        sv.specvlm_tree_verify_attn(q, k, v, P, par, out=out, workspace=ws, num_splits=4)
+    rng = np.random.default_rng(83)
+    for rep in range(3):
+        q_np = W.normal(rng, big["q"].shape, 1.0, "bf16")
+        q.copy_(to_dev(q_np))
+        out.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        eager = sv.specvlm_tree_verify_attn(q, k, v, P, par, workspace=ws, num_splits=4)
+        assert torch.equal(out, eager), f"replay {rep}"
+        ref = oracle.tree_attn(q_np, big["k"], big["v"], big["prefix_len"], big["parent"])[0]
+        assert_attn_close(to_host_f64(out), ref, "bf16", f"replay {rep}")
