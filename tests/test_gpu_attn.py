@@ -202,3 +202,25 @@ def test_one_workspace_across_shapes_and_graph_replays(sv, oracle):
         assert torch.equal(out, eager), f"replay {rep}"
         ref = oracle.tree_attn(q_np, big["k"], big["v"], big["prefix_len"], big["parent"])[0]
         assert_attn_close(to_host_f64(out), ref, "bf16", f"replay {rep}")
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_sweep(sv, oracle, seed):
+    """Seeded random geometry: batch, grouped heads, head size, node counts, prefix lengths from
+    empty to several dozen tiles, split counts (incl. more splits than tiles), paged or contiguous."""
+    from gpu_util import random_case
+    rng = np.random.default_rng(9000 + seed)
+    B = int(rng.integers(1, 4))
+    group = int(rng.choice([1, 1, 2, 4]))
+    Hkv = int(rng.choice([1, 2, 3]))
+    D = int(rng.choice([64, 128]))
+    N = int(rng.integers(1, 65))
+    P = [int(x) for x in rng.choice([0, 1, 15, 16, 31, 33, 100, 255, 640, 1500], size=B)]
+    nn = [int(rng.integers(1, N + 1)) for _ in range(B)]
+    nn[0] = N
+    splits = int(rng.choice([0, 1, 2, 3, 4, 7, 8, 12, 40]))
+    paged = bool(rng.integers(0, 2))
+    case = random_case(7000 + seed, "bf16", B=B, Hq=Hkv * group, Hkv=Hkv, D=D, N_max=N, P_list=P, num_nodes=nn,
+                       paged=paged, depth=int(rng.integers(1, 8)))
+    check(case, *run_both(sv, oracle, case, num_splits=splits),
+          f"seed {seed}: B={B} Hq={Hkv * group} Hkv={Hkv} D={D} N={N} P={P} nn={nn} splits={splits} paged={paged}")
