@@ -49,6 +49,9 @@ def _check(sv, oracle, h, w, nn=None):
     (2, 40, 384, 1),           # one token
     (3, 60, 1024, 5000),       # three requests = 180 rows: three node blocks, the last ragged
     (4, 61, 5120, 32000),      # 13B-shaped hidden size, 61-node trees, four requests
+    (2, 64, 384, 3000),        # exactly two node blocks
+    (6, 64, 128, 300),         # six node blocks share one pass over W
+    (9, 60, 256, 2000),        # 540 rows: a group of eight node blocks and a second group with one
 ])
 def test_matches_oracle(sv, oracle, B, N, E, V):
     rng = np.random.default_rng(B * 1000 + V)
