@@ -54,3 +54,42 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.specvlm_draft_topk(0, 1, 1, 100, 65, *([null, 0, 100] + [null, 0] * 2 + [null] * 3 + [65, null, null])) == 1
     assert lib.specvlm_draft_select(1, 8193, 4, null, 8193, null, 0, null, null, null, null) == 1
     assert lib.specvlm_draft_finalize(1, 100, 65, null, null, null, 100, *([null] * 8)) == 1
+
+
+def test_split_choice_and_workspace_sizes_for_the_five_workloads():
+    """Host logic only: the library's key-range split count and workspace size for the shapes of the
+    five workload configurations (one workgroup per compute unit where the batch allows it)."""
+    import paper_2509_11815_amd as sv
+    from paper_2509_11815_amd.binding import AttnDesc
+    lib = sv.load_library()
+
+    def desc(B, H, D, N, cap, paged=False, dtype=0):
+        d = AttnDesc()
+        d.dtype, d.B, d.H_q, d.H_kv, d.D, d.N_max = dtype, B, H, H, D, N
+        d.q_stride_b, d.q_stride_n, d.q_stride_h = N * H * D, H * D, D
+        d.o_stride_b, d.o_stride_n, d.o_stride_h = N * H * D, H * D, D
+        if paged:
+            d.paged, d.block_size, d.max_blocks_per_req, d.num_blocks = 1, 16, cap // 16, B * cap // 16 + 8
+            d.kv_stride_b, d.kv_stride_h, d.kv_stride_t = H * 16 * D, 16 * D, D
+        else:
+            d.kv_capacity = cap
+            d.kv_stride_b, d.kv_stride_h, d.kv_stride_t = H * cap * D, cap * D, D
+        return d
+
+    cases = {"C1": (desc(1, 4, 64, 8, 80, dtype=1), 1), "C2": (desc(1, 32, 128, 60, 832), 7),
+             "C3": (desc(1, 32, 128, 60, 3328), 8), "C4": (desc(8, 32, 128, 60, 976), 1),
+             "C5": (desc(4, 40, 128, 60, 4928, paged=True), 3)}
+    for name, (d, want) in cases.items():
+        got = lib.specvlm_tree_verify_attn_num_splits(ctypes.byref(d))
+        assert got == want, (name, got)
+        need = lib.specvlm_tree_verify_attn_workspace_bytes(ctypes.byref(d))
+        if d.dtype == 0 and want > 1:
+            parts = d.B * d.H_q * want
+            counters = -(-d.B * d.H_q * 4 * 4 // 256) * 256
+            assert need == counters + parts * (64 * d.D * 2 + 64 * 8), name     # bf16 partials + (max, sum) pairs
+    d = cases["C3"][0]
+    d.num_splits = 5                                                             # a caller's choice is kept
+    assert lib.specvlm_tree_verify_attn_num_splits(ctypes.byref(d)) == 5
+    assert lib.specvlm_head_argmax_workspace_bytes(1, 60, 32000) == 256 + 250 * 64 * 8
+    assert lib.specvlm_head_argmax_workspace_bytes(8, 60, 32000) == 256 + 8 * 250 * 64 * 8
+    assert lib.specvlm_head_argmax_workspace_bytes(0, 60, 32000) == 0
