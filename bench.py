@@ -28,13 +28,13 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/),
 # keyed by workload; None until measured.
 MEASURED_TRAFFIC = {
-    # profiles/attn_mfma_kernel_C3.txt: 29077.5 FETCH_SIZE units x 2.000 KiB + 4841.0 WRITE_SIZE units x 1.000 KiB
-    "C3": {"read_bytes": 59550720, "write_bytes": 4957184, "bytes": 64507904},
+    # profiles/attn_mfma_kernel_C3.txt: 29068.7 FETCH_SIZE units x 2.000 KiB + 4868.0 WRITE_SIZE units x 1.000 KiB
+    "C3": {"read_bytes": 59532698, "write_bytes": 4984832, "bytes": 64517530},
 }
 # the same for the fused output head (profiles/head_argmax_kernel_C3.txt); None until measured
 MEASURED_TRAFFIC_HEAD = {
-    # 130030.2 FETCH_SIZE units x 2.000 KiB + 133.1 WRITE_SIZE units x 1.000 KiB
-    "C3": {"read_bytes": 266301850, "write_bytes": 136294, "bytes": 266438144},
+    # 130048.2 FETCH_SIZE units x 2.000 KiB + 133.1 WRITE_SIZE units x 1.000 KiB
+    "C3": {"read_bytes": 266338714, "write_bytes": 136294, "bytes": 266475008},
 }
 
 
@@ -272,7 +272,7 @@ def main():
         "breakdown_ms": {"attention_all_layers": round(ms_attn, 5), "argmax_accept_compact": round(ms_tail, 5)},
         "outside_the_step_ms": {"tree_accept_sample_T1": round(ms_smp, 5), "draft_tree_growth": round(ms_grow, 5),
                                 "head_argmax_fused": round(ms_head, 5)},
-        "roofline_head_argmax": {"kernel": "specvlm::head_argmax_kernel", "bound": "hbm",
+        "roofline_head_argmax": {"kernel": "specvlm::head_argmax_kernel<1>", "bound": "hbm",
                                  "achieved": round(head_bytes / (ms_head * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
                                  "unit": "GB/s", "frac": round(head_bytes / (ms_head * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                                  "algorithmic_bytes_per_launch": head_bytes, "avg_launch_us": round(ms_head * 1e3, 3),
