@@ -272,7 +272,7 @@ def main():
         "breakdown_ms": {"attention_all_layers": round(ms_attn, 5), "argmax_accept_compact": round(ms_tail, 5)},
         "outside_the_step_ms": {"tree_accept_sample_T1": round(ms_smp, 5), "draft_tree_growth": round(ms_grow, 5),
                                 "head_argmax_fused": round(ms_head, 5)},
-        "roofline_head_argmax": {"kernel": "specvlm::head_argmax_kernel<1>", "bound": "hbm",
+        "roofline_head_argmax": {"kernel": "specvlm::head_argmax_kernel<%d>" % (1 if B * N <= 64 else 2 if B * N <= 128 else 4 if B * N <= 256 else 8), "bound": "hbm",
                                  "achieved": round(head_bytes / (ms_head * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
                                  "unit": "GB/s", "frac": round(head_bytes / (ms_head * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                                  "algorithmic_bytes_per_launch": head_bytes, "avg_launch_us": round(ms_head * 1e3, 3),
