@@ -122,9 +122,11 @@ def main():
             sv.specvlm_tree_verify_attn(q[l], k[l], v[l], prefix_len, parent, block_table=table, out=out[l],
                                         workspace=workspace, err_flag=err, desc=desc)
 
+    counters = torch.zeros(B, dtype=torch.int32, device=dev)
+
     def sample_and_compact():
-        sv.specvlm_node_argmax(logits, out=amax)
-        sv.specvlm_tree_accept(parent, draft_tok, amax, err_flag=err, out=acc_out)
+        # per-node argmax and the greedy acceptance walk as one launch, compaction as one more
+        sv.specvlm_node_argmax_accept(logits, parent, draft_tok, counters=counters, amax=amax, err_flag=err, out=acc_out)
         # the prefix length is NOT advanced between steps, so every step sees the same workload
         sv.specvlm_kv_compact(k, v, prefix_len, acc_out[1], acc_out[0], block_table=table, new_prefix_len=new_prefix)
 

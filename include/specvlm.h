@@ -172,6 +172,22 @@ int32_t specvlm_tree_accept(int32_t B, int32_t N_max, int32_t path_cap,
                             int32_t *committed_tok_dev, int32_t *err_flag_dev, void *stream);
 
 /*
+ * specvlm_node_argmax and specvlm_tree_accept as ONE launch (both are launch-bound): every
+ * (request, node) row is reduced as in specvlm_node_argmax, and the workgroup that finishes the
+ * last row of a request also walks that request's tree as in specvlm_tree_accept.  Arguments and
+ * outputs are those of the two calls (amax_dev is written as well), plus
+ *   counters_dev  device int32 [B]: arrival counters, ZERO-FILLED ONCE after allocation (every call
+ *                 leaves them zero); calls that may run concurrently need separate counters.
+ */
+int32_t specvlm_node_argmax_accept(int32_t dtype, int32_t B, int32_t N_max, int32_t V, int32_t path_cap,
+                                   const void *logits_dev, int64_t stride_b, int64_t stride_n,
+                                   const int32_t *num_nodes_dev, const int32_t *parent_dev,
+                                   const int32_t *draft_tok_dev, int32_t *amax_dev,
+                                   int32_t *accept_len_dev, int32_t *path_dev, int32_t *bonus_tok_dev,
+                                   int32_t *committed_tok_dev, int32_t *counters_dev,
+                                   int32_t *err_flag_dev, void *stream);
+
+/*
  * Sampling-based acceptance walk, temperature > 0 (Sec. 3.1: speculative sampling discards
  * the incorrect drafted tokens; Sec. 4.1: temperature 1 is evaluated with the same Top-K tree,
  * decoding stays lossless).  The children of a node are fixed candidates, i.e. point-mass
@@ -214,7 +230,8 @@ int32_t specvlm_tree_accept_sample(int32_t dtype, int32_t B, int32_t N_max, int3
  * k_layer_ptrs_dev / v_layer_ptrs_dev are non-NULL, the l-th pointer of those DEVICE
  * arrays of L device pointers (then k_base_dev/v_base_dev/layer_stride are ignored).
  * Only desc's dtype, B, H_kv, D, paged, block_size, max_blocks_per_req, kv_capacity
- * and kv_stride_* are used.  new_prefix_len_dev may alias prefix_len_dev.
+ * and kv_stride_* are used.  new_prefix_len_dev may alias prefix_len_dev (that costs a second,
+ * tiny launch: the old lengths may only be overwritten after every workgroup has read them).
  *   moved_idx_dev  optional int32 [B, path_cap, 2]: (src_slot, dst_slot) per j, -1 padded.
  */
 int32_t specvlm_kv_compact(const specvlm_attn_desc *desc, int32_t L,

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     specvlm_head_argmax_workspace_bytes,
     specvlm_kv_compact,
     specvlm_node_argmax,
+    specvlm_node_argmax_accept,
     specvlm_tree_accept,
     specvlm_tree_accept_sample,
     specvlm_tree_verify_attn,

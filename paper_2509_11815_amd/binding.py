@@ -22,7 +22,7 @@ EXPORTS = ["specvlm_version", "specvlm_last_hip_error", "specvlm_tree_verify_att
            "specvlm_tree_verify_attn", "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_tree_accept_sample",
            "specvlm_kv_compact", "specvlm_draft_topk", "specvlm_draft_select", "specvlm_draft_finalize",
            "specvlm_head_argmax", "specvlm_head_argmax_workspace_bytes",
-           "specvlm_visual_pool", "specvlm_visual_prune"]
+           "specvlm_visual_pool", "specvlm_visual_prune", "specvlm_node_argmax_accept"]
 
 
 class SpecvlmError(RuntimeError):
@@ -85,6 +85,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.specvlm_visual_pool.argtypes = [i32] * 5 + [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp]
     L.specvlm_visual_prune.restype = i32
     L.specvlm_visual_prune.argtypes = [i32] * 5 + [vp, i64, i64, vp, vp, i64, i64, vp, vp]
+    L.specvlm_node_argmax_accept.restype = i32
+    L.specvlm_node_argmax_accept.argtypes = [i32] * 5 + [vp, i64, i64] + [vp] * 11
     _lib = L
     return L
 
@@ -436,3 +438,32 @@ def specvlm_visual_prune(x, keep, *, out=None, err_flag=None, stream=None):
                                     _ptr(err_flag), _stream(stream))
     _check(rc, "specvlm_visual_prune")
     return out
+
+
+def specvlm_node_argmax_accept(logits, parent, draft_tok, *, num_nodes=None, path_cap=8, counters=None, amax=None,
+                               err_flag=None, out=None, stream=None):
+    """specvlm_node_argmax + specvlm_tree_accept in one launch.  `counters` is an int32 [B] device tensor,
+    zero-filled once (allocated here when omitted).  Returns (amax, accept_len, path, bonus_tok, committed_tok)."""
+    B, N_max, V = logits.shape
+    dev = logits.device
+    if logits.stride(2) != 1:
+        raise ValueError("vocab dimension must be contiguous")
+    if out is not None:
+        accept_len, path, bonus, committed = out
+        path_cap = path.shape[1]
+    else:
+        accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+        path = torch.empty((B, path_cap), dtype=torch.int32, device=dev)
+        bonus = torch.empty(B, dtype=torch.int32, device=dev)
+        committed = torch.empty((B, path_cap), dtype=torch.int32, device=dev)
+    if amax is None:
+        amax = torch.empty((B, N_max), dtype=torch.int32, device=dev)
+    if counters is None:
+        counters = torch.zeros(B, dtype=torch.int32, device=dev)
+    rc = lib().specvlm_node_argmax_accept(
+        _dtype_code(logits), B, N_max, V, path_cap, _ptr(logits), logits.stride(0), logits.stride(1),
+        _ptr(_dev_i32(num_nodes, "num_nodes")), _ptr(_dev_i32(parent, "parent")),
+        _ptr(_dev_i32(draft_tok, "draft_tok")), _ptr(_dev_i32(amax, "amax")), _ptr(accept_len), _ptr(path),
+        _ptr(bonus), _ptr(committed), _ptr(_dev_i32(counters, "counters")), _ptr(err_flag), _stream(stream))
+    _check(rc, "specvlm_node_argmax_accept")
+    return amax, accept_len, path, bonus, committed

@@ -127,6 +127,26 @@ int32_t specvlm_tree_accept(int32_t B, int32_t N_max, int32_t path_cap, const in
                               static_cast<hipStream_t>(stream));
 }
 
+int32_t specvlm_node_argmax_accept(int32_t dtype, int32_t B, int32_t N_max, int32_t V, int32_t path_cap,
+                                   const void* logits_dev, int64_t stride_b, int64_t stride_n,
+                                   const int32_t* num_nodes_dev, const int32_t* parent_dev,
+                                   const int32_t* draft_tok_dev, int32_t* amax_dev, int32_t* accept_len_dev,
+                                   int32_t* path_dev, int32_t* bonus_tok_dev, int32_t* committed_tok_dev,
+                                   int32_t* counters_dev, int32_t* err_flag_dev, void* stream) {
+    if (dtype != SPECVLM_BF16 && dtype != SPECVLM_F32) return SPECVLM_INVALID_ARG;
+    if (B < 1 || N_max < 1 || N_max > SPECVLM_MAX_NODES || V < 1 || path_cap < 1 || path_cap > SPECVLM_MAX_NODES)
+        return SPECVLM_INVALID_ARG;
+    if (!logits_dev || !amax_dev || stride_b < 0 || stride_n < V) return SPECVLM_INVALID_ARG;
+    const uintptr_t es = dtype == SPECVLM_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(logits_dev) % es) return SPECVLM_INVALID_ARG;
+    if (!parent_dev || !draft_tok_dev || !accept_len_dev || !path_dev || !bonus_tok_dev || !committed_tok_dev ||
+        !counters_dev)
+        return SPECVLM_INVALID_ARG;
+    return launch_node_argmax_accept(dtype, B, N_max, V, path_cap, logits_dev, stride_b, stride_n, num_nodes_dev,
+                                     parent_dev, draft_tok_dev, amax_dev, accept_len_dev, path_dev, bonus_tok_dev,
+                                     committed_tok_dev, counters_dev, err_flag_dev, static_cast<hipStream_t>(stream));
+}
+
 int32_t specvlm_tree_accept_sample(int32_t dtype, int32_t B, int32_t N_max, int32_t V, int32_t path_cap,
                                    const int32_t* parent_dev, const int32_t* draft_tok_dev,
                                    const void* logits_dev, int64_t stride_b, int64_t stride_n,

@@ -47,6 +47,12 @@ int32_t launch_node_argmax(int32_t dtype, int32_t B, int32_t N_max, int32_t V, c
                            int64_t stride_b, int64_t stride_n, const int32_t* num_nodes,
                            int32_t* amax, hipStream_t stream);
 
+int32_t launch_node_argmax_accept(int32_t dtype, int32_t B, int32_t N_max, int32_t V, int32_t path_cap,
+                                  const void* logits, int64_t stride_b, int64_t stride_n, const int32_t* num_nodes,
+                                  const int32_t* parent, const int32_t* draft_tok, int32_t* amax, int32_t* accept_len,
+                                  int32_t* path, int32_t* bonus_tok, int32_t* committed_tok, int32_t* counters,
+                                  int32_t* err_flag, hipStream_t stream);
+
 int32_t launch_tree_accept(int32_t B, int32_t N_max, int32_t path_cap, const int32_t* parent,
                            const int32_t* draft_tok, const int32_t* amax, const int32_t* num_nodes,
                            int32_t* accept_len, int32_t* path, int32_t* bonus_tok,

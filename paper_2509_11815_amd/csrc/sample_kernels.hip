@@ -43,17 +43,59 @@ struct Elem<float> {
     __device__ static float one(const float* p) { return *p; }
 };
 
-template <typename T>
+// (defined with the acceptance kernel below)
+template <bool COHERENT>
+__device__ __forceinline__ void accept_walk(int b, int N_max, int path_cap, const int32_t* __restrict__ parent,
+                                            const int32_t* __restrict__ draft_tok, const int32_t* amax,
+                                            const int32_t* __restrict__ num_nodes, int32_t* __restrict__ accept_len,
+                                            int32_t* __restrict__ path, int32_t* __restrict__ bonus_tok,
+                                            int32_t* __restrict__ committed_tok, int32_t* __restrict__ err_flag,
+                                            int (&s_par)[64], int (&s_tok)[64], int (&s_am)[64]);
+
+// What the fused form needs on top of the arg-max: the acceptance walk's arguments and one
+// arrival counter per request (zero between calls).
+struct AcceptArgs {
+    int path_cap;
+    const int32_t *parent, *draft_tok;
+    int32_t *accept_len, *path, *bonus_tok, *committed_tok, *err_flag;
+    int32_t* counters;
+};
+
+// FUSED: the workgroup that finishes the last row of a request (ticket counter) also runs the
+// greedy acceptance walk of that request, so arg-max + acceptance is one launch.
+template <typename T, bool FUSED>
 __global__ __launch_bounds__(1024) void node_argmax_kernel(int N_max, int V, const T* __restrict__ logits,
                                                            int64_t stride_b, int64_t stride_n,
                                                            const int32_t* __restrict__ num_nodes,
-                                                           int32_t* __restrict__ amax) {
+                                                           int32_t* amax, AcceptArgs acc) {
+    __shared__ int s_last;
+    __shared__ int s_par[64], s_tok[64], s_am[64];
     const int row = blockIdx.x;
     const int b = row / N_max, i = row % N_max;
     const int tid = threadIdx.x;
     int n = num_nodes ? num_nodes[b] : N_max;
+    // publishes this row's result; FUSED: then draws the request's ticket, and the workgroup that
+    // draws the last one walks the tree (called by all threads of the workgroup)
+    auto finish = [&](int result) {
+        if constexpr (!FUSED) {
+            if (tid == 0) amax[row] = result;
+        } else {
+            if (tid == 0) {
+                __hip_atomic_store(amax + row, result, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // the store has been acknowledged
+                const int ticket = __hip_atomic_fetch_add(acc.counters + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int last = ticket == N_max - 1;
+                if (last) __hip_atomic_store(acc.counters + b, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_last = last;
+            }
+            __syncthreads();
+            if (s_last)                                                   // uniform
+                accept_walk<true>(b, N_max, acc.path_cap, acc.parent, acc.draft_tok, amax, num_nodes, acc.accept_len,
+                                  acc.path, acc.bonus_tok, acc.committed_tok, acc.err_flag, s_par, s_tok, s_am);
+        }
+    };
     if (i >= n) {
-        if (tid == 0) amax[row] = -1;
+        finish(-1);
         return;
     }
     const T* p = logits + b * stride_b + i * stride_n;
@@ -98,20 +140,39 @@ __global__ __launch_bounds__(1024) void node_argmax_kernel(int N_max, int V, con
             int oi = __shfl_xor(r.i, off);
             take_better(r, ov, oi);
         }
-        if (lane == 0) amax[row] = r.i == INT_MAX ? 0 : r.i;
+        if (lane == 0) s_i[0] = r.i == INT_MAX ? 0 : r.i;
     }
+    __syncthreads();
+    finish(s_i[0]);
 }
 
 int32_t launch_node_argmax(int32_t dtype, int32_t B, int32_t N_max, int32_t V, const void* logits,
                            int64_t stride_b, int64_t stride_n, const int32_t* num_nodes,
                            int32_t* amax, hipStream_t stream) {
     dim3 grid(B * N_max), block(1024);
+    const AcceptArgs none{};
     if (dtype == SPECVLM_BF16)
-        hipLaunchKernelGGL(node_argmax_kernel<uint16_t>, grid, block, 0, stream, N_max, V,
-                           static_cast<const uint16_t*>(logits), stride_b, stride_n, num_nodes, amax);
+        hipLaunchKernelGGL((node_argmax_kernel<uint16_t, false>), grid, block, 0, stream, N_max, V,
+                           static_cast<const uint16_t*>(logits), stride_b, stride_n, num_nodes, amax, none);
     else
-        hipLaunchKernelGGL(node_argmax_kernel<float>, grid, block, 0, stream, N_max, V,
-                           static_cast<const float*>(logits), stride_b, stride_n, num_nodes, amax);
+        hipLaunchKernelGGL((node_argmax_kernel<float, false>), grid, block, 0, stream, N_max, V,
+                           static_cast<const float*>(logits), stride_b, stride_n, num_nodes, amax, none);
+    return check_launch();
+}
+
+int32_t launch_node_argmax_accept(int32_t dtype, int32_t B, int32_t N_max, int32_t V, int32_t path_cap,
+                                  const void* logits, int64_t stride_b, int64_t stride_n, const int32_t* num_nodes,
+                                  const int32_t* parent, const int32_t* draft_tok, int32_t* amax, int32_t* accept_len,
+                                  int32_t* path, int32_t* bonus_tok, int32_t* committed_tok, int32_t* counters,
+                                  int32_t* err_flag, hipStream_t stream) {
+    dim3 grid(B * N_max), block(1024);
+    const AcceptArgs acc{path_cap, parent, draft_tok, accept_len, path, bonus_tok, committed_tok, err_flag, counters};
+    if (dtype == SPECVLM_BF16)
+        hipLaunchKernelGGL((node_argmax_kernel<uint16_t, true>), grid, block, 0, stream, N_max, V,
+                           static_cast<const uint16_t*>(logits), stride_b, stride_n, num_nodes, amax, acc);
+    else
+        hipLaunchKernelGGL((node_argmax_kernel<float, true>), grid, block, 0, stream, N_max, V,
+                           static_cast<const float*>(logits), stride_b, stride_n, num_nodes, amax, acc);
     return check_launch();
 }
 
@@ -119,37 +180,43 @@ int32_t launch_node_argmax(int32_t dtype, int32_t B, int32_t N_max, int32_t V, c
 // tree_accept: one wavefront per request, lane i owns node i.  Every lane walks its own
 // root path (parent[i] < i bounds the walk by i steps), so a lane knows whether its node
 // is accepted and how deep it is; a wavefront max over (depth, -index) picks the node.
+// accept_walk is called by ALL threads of a workgroup (it contains a workgroup barrier);
+// only the first 64 act.  COHERENT: amax was written by other workgroups of the same
+// kernel (device-coherent loads); otherwise by an earlier kernel.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void tree_accept_kernel(int N_max, int path_cap,
-                                                         const int32_t* __restrict__ parent,
-                                                         const int32_t* __restrict__ draft_tok,
-                                                         const int32_t* __restrict__ amax,
-                                                         const int32_t* __restrict__ num_nodes,
-                                                         int32_t* __restrict__ accept_len,
-                                                         int32_t* __restrict__ path,
-                                                         int32_t* __restrict__ bonus_tok,
-                                                         int32_t* __restrict__ committed_tok,
-                                                         int32_t* __restrict__ err_flag) {
-    __shared__ int s_par[64], s_tok[64], s_am[64];
-    const int b = blockIdx.x, lane = threadIdx.x;
+template <bool COHERENT>
+__device__ __forceinline__ void accept_walk(int b, int N_max, int path_cap, const int32_t* __restrict__ parent,
+                                            const int32_t* __restrict__ draft_tok, const int32_t* amax,
+                                            const int32_t* __restrict__ num_nodes, int32_t* __restrict__ accept_len,
+                                            int32_t* __restrict__ path, int32_t* __restrict__ bonus_tok,
+                                            int32_t* __restrict__ committed_tok, int32_t* __restrict__ err_flag,
+                                            int (&s_par)[64], int (&s_tok)[64], int (&s_am)[64]) {
+    const int lane = threadIdx.x;
+    const bool active = lane < 64;                          // uniform per wavefront
     int err = 0;
     int n = num_nodes ? num_nodes[b] : N_max;
     if (n < 1 || n > N_max) {
         err |= SPECVLM_ERR_BAD_NUM_NODES;
         n = min(max(n, 1), N_max);
     }
-    int par = -1, tok = -1, am = -1;
     bool bad = false;
-    if (lane < n) {
-        par = parent[b * N_max + lane];
-        tok = draft_tok[b * N_max + lane];
-        am = amax[b * N_max + lane];
-        bad = lane == 0 ? par != -1 : (par < 0 || par >= lane);
+    if (active) {
+        int par = -1, tok = -1, am = -1;
+        if (lane < n) {
+            par = parent[b * N_max + lane];
+            tok = draft_tok[b * N_max + lane];
+            if constexpr (COHERENT)
+                am = __hip_atomic_load(amax + b * N_max + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else
+                am = amax[b * N_max + lane];
+            bad = lane == 0 ? par != -1 : (par < 0 || par >= lane);
+        }
+        s_par[lane] = par;
+        s_tok[lane] = tok;
+        s_am[lane] = am;
     }
-    s_par[lane] = par;
-    s_tok[lane] = tok;
-    s_am[lane] = am;
     __syncthreads();
+    if (!active) return;
     int32_t* prow = path + b * path_cap;
     int32_t* crow = committed_tok + b * path_cap;
     if (__any(bad)) {                       // malformed tree: commit the root only
@@ -204,6 +271,21 @@ __global__ __launch_bounds__(64) void tree_accept_kernel(int N_max, int path_cap
     if (lane == 0 && err && err_flag) atomicOr(err_flag, err);
 }
 
+__global__ __launch_bounds__(64) void tree_accept_kernel(int N_max, int path_cap,
+                                                         const int32_t* __restrict__ parent,
+                                                         const int32_t* __restrict__ draft_tok,
+                                                         const int32_t* __restrict__ amax,
+                                                         const int32_t* __restrict__ num_nodes,
+                                                         int32_t* __restrict__ accept_len,
+                                                         int32_t* __restrict__ path,
+                                                         int32_t* __restrict__ bonus_tok,
+                                                         int32_t* __restrict__ committed_tok,
+                                                         int32_t* __restrict__ err_flag) {
+    __shared__ int s_par[64], s_tok[64], s_am[64];
+    accept_walk<false>(blockIdx.x, N_max, path_cap, parent, draft_tok, amax, num_nodes, accept_len, path, bonus_tok,
+                       committed_tok, err_flag, s_par, s_tok, s_am);
+}
+
 int32_t launch_tree_accept(int32_t B, int32_t N_max, int32_t path_cap, const int32_t* parent,
                            const int32_t* draft_tok, const int32_t* amax, const int32_t* num_nodes,
                            int32_t* accept_len, int32_t* path, int32_t* bonus_tok,
@@ -227,9 +309,20 @@ __global__ __launch_bounds__(kCompactThreads) void kv_compact_kernel(
     KvGeom g, unsigned char* k_base, unsigned char* v_base, int64_t layer_stride_bytes,
     void* const* k_ptrs, void* const* v_ptrs, int elem_bytes, int row_chunks,
     const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ path, int path_cap,
-    const int32_t* __restrict__ accept_len) {
+    const int32_t* __restrict__ accept_len, int32_t* __restrict__ new_prefix_len, int32_t* __restrict__ moved_idx) {
     const int l = blockIdx.x >> 1, which = blockIdx.x & 1;
     const int hk = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    // new_prefix_len is given here only when it does not alias prefix_len (which every workgroup
+    // of the request reads): then the request's first workgroup writes the bookkeeping outputs
+    if (new_prefix_len && blockIdx.x == 0 && hk == 0 && tid < path_cap) {
+        const int P0 = prefix_len[b];
+        const int m0 = min(max(accept_len[b], 0), path_cap - 1);
+        if (moved_idx) {
+            moved_idx[(b * path_cap + tid) * 2 + 0] = tid <= m0 ? P0 + path[b * path_cap + tid] : -1;
+            moved_idx[(b * path_cap + tid) * 2 + 1] = tid <= m0 ? P0 + tid : -1;
+        }
+        if (tid == 0) new_prefix_len[b] = P0 + m0 + 1;
+    }
     unsigned char* base;
     if (k_ptrs)
         base = static_cast<unsigned char*>(which ? v_ptrs[l] : k_ptrs[l]);
@@ -287,12 +380,15 @@ int32_t launch_kv_compact(const specvlm_attn_desc& d, int32_t L, void* k_base, v
              d.max_blocks_per_req, d.num_blocks,
              d.paged ? d.max_blocks_per_req * SPECVLM_PAGE_SIZE : d.kv_capacity};
     dim3 grid(L * 2, d.H_kv, d.B);
+    // One launch when new_prefix_len is a buffer of its own; when it aliases prefix_len it may only
+    // be written after every workgroup has read the old lengths: a second, tiny launch.
+    const bool alias = new_prefix_len == prefix_len;
     hipLaunchKernelGGL(kv_compact_kernel, grid, dim3(kCompactThreads), 0, stream, g,
                        static_cast<unsigned char*>(k_base), static_cast<unsigned char*>(v_base),
                        layer_stride * eb, k_ptrs, v_ptrs, eb, d.D * eb / 16, prefix_len, path,
-                       path_cap, accept_len);
+                       path_cap, accept_len, alias ? nullptr : new_prefix_len, alias ? nullptr : moved_idx);
     int32_t rc = check_launch();
-    if (rc) return rc;
+    if (rc || !alias) return rc;
     hipLaunchKernelGGL(kv_compact_finish_kernel, dim3((d.B + 63) / 64), dim3(64), 0, stream, d.B,
                        prefix_len, path, path_cap, accept_len, new_prefix_len, moved_idx);
     return check_launch();

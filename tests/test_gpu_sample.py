@@ -96,7 +96,8 @@ def test_accept_error_flags(sv):
 # ------------------------------------------------------------------ compaction
 @pytest.mark.parametrize("dtype,D", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
 @pytest.mark.parametrize("paged", [False, True])
-def test_compact_matches_oracle(sv, oracle, dtype, D, paged):
+@pytest.mark.parametrize("alias", [True, False])
+def test_compact_matches_oracle(sv, oracle, dtype, D, paged, alias):
     from gpu_util import i32, to_dev, to_host_bits
     rng = np.random.default_rng(5)
     L, B, H, bs, cap = 3, 3, 2, 16, 8
@@ -120,9 +121,12 @@ def test_compact_matches_oracle(sv, oracle, dtype, D, paged):
     kd, vd = to_dev(k), to_dev(v)
     moved = torch.zeros((B, cap, 2), dtype=torch.int32, device="cuda")
     Pd = i32(P)
+    # new_prefix_len aliasing prefix_len (two launches) or a buffer of its own (one launch)
     newp, _ = sv.specvlm_kv_compact(kd, vd, Pd, i32(paths), i32(m), block_table=None if table is None else i32(table),
-                                    new_prefix_len=Pd, moved_idx=moved)       # aliasing prefix_len
+                                    new_prefix_len=Pd if alias else None, moved_idx=moved)
     torch.cuda.synchronize()
+    if not alias:
+        assert np.array_equal(Pd.cpu().numpy(), P)
     ref_newp, ref_moved = oracle.kv_compact(k, v, P, paths, m, block_table=table)
     assert np.array_equal(newp.cpu().numpy(), ref_newp)
     assert np.array_equal(moved.cpu().numpy(), ref_moved)
@@ -147,3 +151,39 @@ def test_compact_layer_pointer_array(sv, oracle):
     assert np.array_equal(newp.cpu().numpy(), ref_newp)
     for l in range(L):
         assert np.array_equal(to_host_bits(kd[l]), kh[l]) and np.array_equal(to_host_bits(vd[l]), vh[l])
+
+
+
+# ------------------------------------------------------------------ argmax + accept in one launch
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_fused_argmax_accept_matches_oracle(sv, oracle, dtype):
+    """Same results as the two separate calls; the counters are zeroed once and reused by every call."""
+    from gpu_util import i32, to_dev
+    rng = np.random.default_rng(17)
+    B, N, V, cap = 5, 60, 1000, 8
+    counters = torch.zeros(B, dtype=torch.int32, device="cuda")
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for rep in range(3):
+        trees = [W.eagle_tree(rng, N, 6, 10) for _ in range(B)]
+        parent = np.stack([t[0] for t in trees])
+        logits, top = W.planted_logits(rng, B * N, V, 2.0, "bf16" if dtype == "bf16" else "fp32")
+        logits, top = logits.reshape(B, N, V), top.reshape(B, N)
+        tok = np.stack([W.draft_tokens_topk(rng, trees[b][0], trees[b][2], top[b], V, 0.8) for b in range(B)])
+        nn = rng.integers(1, N + 1, size=B).astype(np.int32)
+        nn[0] = N
+        amax, m, path, bonus, committed = sv.specvlm_node_argmax_accept(
+            to_dev(logits), i32(parent), i32(tok), num_nodes=i32(nn), path_cap=cap, counters=counters, err_flag=err)
+        r_amax = oracle.node_argmax(logits, nn)
+        r_m, r_path, r_bonus, r_comm = oracle.tree_accept(parent, tok, r_amax, nn, path_cap=cap)
+        assert np.array_equal(amax.cpu().numpy(), r_amax)
+        assert np.array_equal(m.cpu().numpy(), r_m) and np.array_equal(path.cpu().numpy(), r_path)
+        assert np.array_equal(bonus.cpu().numpy(), r_bonus) and np.array_equal(committed.cpu().numpy(), r_comm)
+        assert int(err.item()) == 0 and int(counters.abs().sum().item()) == 0
+        assert r_m.max() >= 1 or rep < 2
+    # a malformed tree: the root is committed, the flag is set, the counters are back to zero
+    bad = parent.copy()
+    bad[1, 2] = 2
+    _, m, path, _, _ = sv.specvlm_node_argmax_accept(to_dev(logits), i32(bad), i32(tok), path_cap=cap,
+                                                     counters=counters, err_flag=err)
+    assert int(err.item()) & 1 and int(m[1].item()) == 0 and path[1].tolist() == [0] + [-1] * (cap - 1)
+    assert int(counters.abs().sum().item()) == 0
