@@ -17,9 +17,9 @@
 //             are tied up by bytes in flight); one load
 //             instruction moves four whole 256-byte rows, fully coalesced.  Each wavefront of
 //             a stream requests 8 of a tile's 32 rows.  Two tiles per stream are in flight
-//             ahead of the one consumed: about 64 load instructions per compute unit, which
-//             is what the memory pipeline accepts without stalling the issuing wavefront
-//             (more in flight measured slower).  Completion is tracked by hand with
+//             ahead of the one consumed (64 KB per compute unit): with every compute unit
+//             streaming the chip is saturated at that depth, more in flight measured
+//             slower.  Completion is tracked by hand with
 //             s_waitcnt vmcnt, and one workgroup barrier per tile publishes the landed
 //             shares and frees the consumed slot
 //   QK^T      S^T[32 keys x 64 q] = K . Q^T with v_mfma_f32_16x16x32_bf16; the lanes fetch
@@ -287,8 +287,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     // ring's last slot -- first half of the rows in this wavefront's K area, second half in its V
     // area, the two areas only this wavefront refills later, so no other wavefront can overwrite
     // them before they are read (query rows past the node count re-read the last real row; their
-    // columns of S^T are never stored).  Those are what the first step needs, and together about
-    // as many load instructions as a compute unit takes at once; the tiles further ahead come after.
+    // columns of S^T are never stored).  Those are what the first step needs; the tiles further
+    // ahead come after.
     if (wave == 0)
         dma4(p.parent + static_cast<int64_t>(b) * p.N_max + min(lane, p.N_max - 1),
              (uint32_t)(uintptr_t)(lds_int*)s_par);
@@ -379,8 +379,6 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         const int slot0 = (stream + j * nstream) * kTile;
         // The slot of tile j+PD held tile j+PD-kSlots <= j-1, consumed by every wavefront of the
         // stream before the barrier that ended the previous iteration: request the tile into it.
-        // About 64 load instructions in flight per compute unit is what the memory pipeline
-        // takes without stalling the issuing wavefront.
         if (j + PD < my_tiles) issue_part(j + PD, phys);
         if (j + PD + 1 < my_tiles) fetch_blocks(j + PD + 1, phys);     // for the next iteration
 
@@ -687,10 +685,10 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
 // Key-range splits per (request, head) when the caller leaves the choice to the library: the
 // count that minimises a small cost model of the kernel on 256 compute units, one workgroup
 // each.  A workgroup costs a fixed prologue + merge time plus one step per 32-key tile of its
-// longest stream; a step takes what one compute unit needs to pull its tiles through its own
-// bounded queue of outstanding loads (measured: the same with 160 or 256 units active), or
-// its share of HBM bandwidth if that is slower; workgroups beyond 256 run as further rounds.  The cache capacity stands
-// in for the request lengths, which the host does not know.
+// longest stream; a step takes the measured time of the loop body with two tiles in flight
+// (the same with 160 or 256 units active), or the workgroup's share of HBM bandwidth if that
+// is slower; workgroups beyond 256 run as further rounds.  The cache capacity stands in for
+// the request lengths, which the host does not know.
 int32_t attn_mfma_pick_splits(const specvlm_attn_desc& d) {
     if (d.num_splits > 0) return min(d.num_splits, 64);
     const int cus = 256;
