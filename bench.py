@@ -47,6 +47,7 @@ def parse_args():
     ap.add_argument("--splits", type=int, default=0, help="key-range splits per (request, head); 0 = library default")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU oracle baseline leg")
+    ap.add_argument("--skip-ceilings", action="store_true", help="skip the library copy / read-only bandwidth legs")
     ap.add_argument("--attn-only", action="store_true", help="profile helper: run only the attention launches")
     ap.add_argument("--head-only", action="store_true", help="profile helper: run only the fused output-head launches")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -286,6 +287,19 @@ def main():
                      "avg_launch_us": round(attn_launch_us, 3),
                      "traffic": MEASURED_TRAFFIC.get(cfg.name)},
     }
+
+    # ---- what plain library kernels reach on this machine: device copy (read + write) and a read-only pass ----
+    if not args.skip_ceilings:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        ms_copy = timed(lambda: dst.copy_(src), 10, 3)
+        ms_sum = timed(lambda: src.sum(), 10, 3)
+        nbytes = src.numel() * 4
+        result["measured_ceilings"] = {
+            "device_copy_GBps": round(2 * nbytes / (ms_copy * 1e-3) / 1e9, 1),
+            "read_only_sum_GBps": round(nbytes / (ms_sum * 1e-3) / 1e9, 1),
+            "note": "torch copy_ / sum over 1 GiB of fp32, bytes read + written per second"}
+        del src, dst
 
     # ---- CPU baseline: the fp64 oracle as it stands, on this host, on a bounded sample ------
     if not args.skip_cpu:
