@@ -33,6 +33,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kHeadThreads = 512;
 constexpr int kVT = 128;                 // vocabulary rows per workgroup
@@ -302,17 +303,43 @@ __global__ __launch_bounds__(kHeadThreads) void head_argmax_kernel(HeadParams p)
     for (int nb = 0; nb < NB; ++nb) {
         if (!((flags >> nb) & 1)) continue;                // uniform
         const int mb = mb0 + nb;
-        // the last workgroup of this node block: node = tid % 64, eight slices of the vocabulary tiles
+        // The last workgroup of this node block reads the block's [tiles][64] keys: a thread takes two
+        // neighbouring nodes (16 bytes) of every 16th tile, 16 device-coherent loads requested
+        // back to back and waited for once (requested one by one, each costs a memory round
+        // trip: 8.7 us for 250 tiles, against 1 us this way).  The compiler does not track these
+        // loads; every register passes through an empty asm after the wait so that no use can
+        // be scheduled before it.  Tile indices past the last tile are clamped: taking a key
+        // twice does not change a maximum.
         {
-            const int node = tid & 63, slice = tid >> 6;
-            const unsigned long long* src = p.ws_key + static_cast<int64_t>(mb) * nvt * kMB + node;
-            unsigned long long best = 0;
-            for (int t = slice; t < nvt; t += 8) {
-                const unsigned long long o = __hip_atomic_load(src + static_cast<int64_t>(t) * kMB, __ATOMIC_RELAXED,
-                                                               __HIP_MEMORY_SCOPE_AGENT);
-                best = o > best ? o : best;
+            const int pair = tid & 31, slice = tid >> 5;
+            const unsigned char* src = reinterpret_cast<const unsigned char*>(p.ws_key + static_cast<int64_t>(mb) * nvt * kMB);
+            unsigned long long best0 = 0, best1 = 0;
+            for (int t0 = 0; t0 < nvt; t0 += 256) {        // uniform
+                u32x4 r[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const uint32_t voff = static_cast<uint32_t>(min(t0 + slice + 16 * u, nvt - 1)) * (kMB * 8) + pair * 16;
+                    asm volatile("global_load_dwordx4 %0, %1, %2 sc1" : "=v"(r[u]) : "v"(voff), "s"(src) : "memory");
+                }
+                head_wait_vmcnt<0>();
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    asm volatile("" : "+v"(r[u]));
+                    const unsigned long long k0 = (static_cast<unsigned long long>(r[u][1]) << 32) | r[u][0];
+                    const unsigned long long k1 = (static_cast<unsigned long long>(r[u][3]) << 32) | r[u][2];
+                    best0 = k0 > best0 ? k0 : best0;
+                    best1 = k1 > best1 ? k1 : best1;
+                }
             }
-            s_key[slice][node] = best;
+            // a wavefront holds two slices (lanes 0-31 and 32-63) of the same 32 node pairs
+            unsigned long long o = __shfl_xor(best0, 32);
+            best0 = o > best0 ? o : best0;
+            o = __shfl_xor(best1, 32);
+            best1 = o > best1 ? o : best1;
+            if (lane < 32) {
+                s_key[wave][2 * pair] = best0;
+                s_key[wave][2 * pair + 1] = best1;
+            }
         }
         __syncthreads();
         if (tid < kMB) {
