@@ -224,3 +224,58 @@ def test_random_shapes_sweep(sv, oracle, seed):
                        paged=paged, depth=int(rng.integers(1, 8)))
     check(case, *run_both(sv, oracle, case, num_splits=splits),
           f"seed {seed}: B={B} Hq={Hkv * group} Hkv={Hkv} D={D} N={N} P={P} nn={nn} splits={splits} paged={paged}")
+
+
+def test_long_video_prefix(sv, oracle):
+    """A prefix of 150001 tokens (a long video): thousands of tiles per stream, ragged tail, the
+    library's own split choice and the largest split count."""
+    from gpu_util import random_case
+    case = random_case(71, "bf16", B=1, Hq=2, Hkv=2, D=128, N_max=40, P_list=[150001])
+    for splits in (0, 64):
+        check(case, *run_both(sv, oracle, case, num_splits=splits), f"long prefix, splits={splits}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_requests_more_than_4_gib_apart(sv, oracle, dtype):
+    """The two requests' caches sit 4.6 GB apart inside one allocation (batch stride beyond 32 bits
+    in bytes, for fp32 also close to 2^31 in elements)."""
+    from gpu_util import random_case, i32, to_dev, to_host_f64, assert_attn_close
+    case = random_case(72, dtype, B=2, Hq=4, Hkv=2, D=128, N_max=33, P_list=[700, 129])
+    B, Hkv, cap, D = case["k"].shape
+    esize = 2 if dtype == "bf16" else 4
+    stride_b = (4_600_000_000 // esize) // 128 * 128
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    views = []
+    for name in ("k", "v"):
+        big = torch.empty(stride_b + Hkv * cap * D, dtype=tdt, device="cuda")
+        view = big.as_strided((B, Hkv, cap, D), (stride_b, cap * D, D, 1))
+        view.copy_(to_dev(case[name]))
+        views.append(view)
+    out = sv.specvlm_tree_verify_attn(to_dev(case["q"]), views[0], views[1], i32(case["prefix_len"]),
+                                      i32(case["parent"]))
+    torch.cuda.synchronize()
+    ref, _ = oracle.tree_attn(case["q"], case["k"], case["v"], case["prefix_len"], case["parent"])
+    assert_attn_close(to_host_f64(out), ref, dtype, f"far-apart requests, {dtype}")
+
+
+def test_paged_pool_larger_than_4_gib(sv, oracle):
+    """Block ids near the end of a 5.7 GB pool: the oracle sees the same blocks renumbered densely."""
+    from gpu_util import random_case, i32, to_dev, to_host_f64, assert_attn_close
+    case = random_case(73, "bf16", B=2, Hq=2, Hkv=2, D=128, N_max=64, P_list=[300, 41], paged=True)
+    nb_small, Hkv, bs, D = case["k"].shape
+    nb_big = 700_000
+    rng = np.random.default_rng(74)
+    where = np.sort(rng.choice(np.arange(nb_big - 5000, nb_big), size=nb_small, replace=False))
+    where[0] = 3                                         # one block near the start as well
+    pools = []
+    for name in ("k", "v"):
+        pool = torch.empty((nb_big, Hkv, bs, D), dtype=torch.bfloat16, device="cuda")
+        pool[torch.from_numpy(where).cuda()] = to_dev(case[name])
+        pools.append(pool)
+    table_big = where[case["block_table"]].astype(np.int32)
+    out = sv.specvlm_tree_verify_attn(to_dev(case["q"]), pools[0], pools[1], i32(case["prefix_len"]),
+                                      i32(case["parent"]), block_table=i32(table_big))
+    torch.cuda.synchronize()
+    ref, _ = oracle.tree_attn(case["q"], case["k"], case["v"], case["prefix_len"], case["parent"],
+                              block_table=case["block_table"])
+    assert_attn_close(to_host_f64(out), ref, "bf16", "large paged pool")

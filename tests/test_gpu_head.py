@@ -121,3 +121,22 @@ def test_agrees_with_stored_logits_path_on_the_workload(sv, oracle):
     _, r_mx, r_gap, _ = oracle.head_argmax(h, w)
     safe = r_gap > np.abs(r_mx) * 2.0 ** -7                              # bf16 keeps 8 significant bits
     assert safe.mean() > 0.5 and np.array_equal(fused[safe], stored[safe])
+
+
+def test_head_matrix_spanning_more_than_4_gib(sv, oracle):
+    """The head matrix's rows are 2 MB apart (5.2 GB from the first to the last): row addresses
+    need 64 bits.  The oracle sees the same matrix densely packed."""
+    from gpu_util import to_dev
+    rng = np.random.default_rng(78)
+    B, N, E, V = 1, 20, 256, 2500
+    h = W.normal(rng, (B, N, E), 1.0, "bf16")
+    w = W.normal(rng, (V, E), 2.0 / np.sqrt(E), "bf16")
+    stride = 1 << 20
+    big = torch.empty((V - 1) * stride + E, dtype=torch.bfloat16, device="cuda")
+    wv = big.as_strided((V, E), (stride, 1))
+    wv.copy_(to_dev(w))
+    got = sv.specvlm_head_argmax(to_dev(h), wv).cpu().numpy()
+    r_amax, _, r_gap, r_second = oracle.head_argmax(h, w)
+    clear = r_gap > CLEAR
+    assert np.array_equal(got[clear], r_amax[clear]) and clear.sum() >= 0.9 * clear.size
+    assert np.all((got == r_amax) | (got == r_second))

@@ -187,3 +187,39 @@ def test_fused_argmax_accept_matches_oracle(sv, oracle, dtype):
                                                      counters=counters, err_flag=err)
     assert int(err.item()) & 1 and int(m[1].item()) == 0 and path[1].tolist() == [0] + [-1] * (cap - 1)
     assert int(counters.abs().sum().item()) == 0
+
+
+# ------------------------------------------------------------------ offsets that need 64 bits
+def test_argmax_and_compact_more_than_4_gib_apart(sv, oracle):
+    """Requests 4.6 GB apart in the logits; layers 4.4 GB and requests 2.3 GB apart in the caches."""
+    from gpu_util import i32, to_dev, to_host_bits
+    rng = np.random.default_rng(8)
+    B, N, V = 2, 5, 3001
+    lg = W.normal(rng, (B, N, V), 2.0, "bf16")
+    stride_b = 2_300_000_000
+    big = torch.empty(stride_b + N * V, dtype=torch.bfloat16, device="cuda")
+    view = big.as_strided((B, N, V), (stride_b, V, 1))
+    view.copy_(to_dev(lg))
+    assert np.array_equal(sv.specvlm_node_argmax(view).cpu().numpy(), oracle.node_argmax(lg))
+    del big, view
+
+    L, H, S_cap, D = 2, 2, 40, 128
+    k = rng.integers(0, 65536, size=(L, B, H, S_cap, D), dtype=np.uint16)
+    v = rng.integers(0, 65536, size=(L, B, H, S_cap, D), dtype=np.uint16)
+    sl, sb = 2_200_000_000, 1_150_000_000                  # elements
+    strides = (sl, sb, S_cap * D, D, 1)
+    bufs = []
+    for a in (k, v):
+        buf = torch.empty(sl + sb + H * S_cap * D, dtype=torch.bfloat16, device="cuda")
+        t = buf.as_strided(a.shape, strides)
+        t.copy_(to_dev(a))
+        bufs.append(t)
+    P = np.array([7, 20], dtype=np.int32)
+    paths = np.array([[0, 3, 4, 9], [0, 2, -1, -1]], dtype=np.int32)
+    m = np.array([3, 1], dtype=np.int32)
+    newp, _ = sv.specvlm_kv_compact(bufs[0], bufs[1], i32(P), i32(paths), i32(m))
+    torch.cuda.synchronize()
+    ref_newp, _ = oracle.kv_compact(k, v, P, paths, m)
+    assert np.array_equal(newp.cpu().numpy(), ref_newp)
+    assert np.array_equal(to_host_bits(bufs[0].contiguous()), k)
+    assert np.array_equal(to_host_bits(bufs[1].contiguous()), v)
