@@ -51,10 +51,22 @@ __device__ __forceinline__ unsigned long long order_key(float v, int idx) {
     return (static_cast<unsigned long long>(u) << 32) | (0xFFFFFFFFu - static_cast<uint32_t>(idx));
 }
 
+// The upper word of an order_key on its own (greater logit <=> greater word), and its inverse.
+__device__ __forceinline__ uint32_t order_bits(float v) {
+    const uint32_t u = __float_as_uint(v + 0.0f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float bits_value(uint32_t u) {
+    return __uint_as_float((u & 0x80000000u) ? (u & 0x7FFFFFFFu) : ~u);
+}
+
+__device__ __forceinline__ unsigned long long make_key(uint32_t bits, int idx) {
+    return (static_cast<unsigned long long>(bits) << 32) | (0xFFFFFFFFu - static_cast<uint32_t>(idx));
+}
+
 __device__ __forceinline__ float key_value(unsigned long long k) {     // the logit inside an order_key
-    uint32_t u = static_cast<uint32_t>(k >> 32);
-    u = (u & 0x80000000u) ? (u & 0x7FFFFFFFu) : ~u;
-    return __uint_as_float(u);
+    return bits_value(static_cast<uint32_t>(k >> 32));
 }
 
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x) {
@@ -123,7 +135,11 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
     auto idx_of = [&](int s) -> int {
         return vec ? (tid + kThreadsDT * (s / VEC)) * VEC + s % VEC : tid + kThreadsDT * s;
     };
-    float lv[NS > 0 ? NS : 1];
+    // An entry is kept as the upper word of its order_key (one register; the lower word follows
+    // from the entry's position): 16 wavefronts leave a thread 128 registers, and 64-bit keys of
+    // all entries do not fit beside the entries themselves.  Entries past V hold the word of -inf.
+    uint32_t ov[NS > 0 ? NS : 1];
+    const uint32_t kNegInfBits = 0x007FFFFFu;             // order_bits(-inf)
     if constexpr (NS > 0) {
         if (vec) {
 #pragma unroll
@@ -132,27 +148,45 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
                 if (v0 < V) {
                     const uint4 x = *reinterpret_cast<const uint4*>(row + v0);
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) lv[j * VEC + e] = Lane16<T>::at(x, e);
+                    for (int e = 0; e < VEC; ++e) ov[j * VEC + e] = order_bits(Lane16<T>::at(x, e));
                 } else {
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) lv[j * VEC + e] = -INFINITY;
+                    for (int e = 0; e < VEC; ++e) ov[j * VEC + e] = kNegInfBits;
                 }
             }
         } else {
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 const int v = tid + kThreadsDT * s;
-                lv[s] = v < V ? Lane16<T>::one(row + v) : -INFINITY;
+                ov[s] = v < V ? order_bits(Lane16<T>::one(row + v)) : kNegInfBits;
             }
         }
     }
+    // Best entry of this thread among those not in `skip` (bit s = entry s): its key, or 0 when
+    // none is left.  A thread's entries are in ascending token order, so "greater" alone keeps
+    // the lowest token among equal logits.  (A key is never 0: no logit is NaN.)
+    auto thread_best = [&](unsigned long long skip) -> unsigned long long {
+        uint32_t bo = 0;
+        int bv = 0;
+        if constexpr (NS > 0) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const int v = idx_of(s);
+                const uint32_t o = (v < V && !((skip >> s) & 1ull)) ? ov[s] : 0u;
+                if (o > bo) { bo = o; bv = v; }
+            }
+        }
+        return bo ? make_key(bo, bv) : 0ull;
+    };
     const int ns_mem = (V + kThreadsDT - 1) / kThreadsDT;          // NS == 0: entries per thread
 
     // ---- log-sum-exp of the row -----------------------------------------------------------
     float part = -INFINITY;
     if constexpr (NS > 0) {
+        uint32_t om = 0;
 #pragma unroll
-        for (int s = 0; s < NS; ++s) part = fmaxf(part, lv[s]);    // entries past V hold -inf
+        for (int s = 0; s < NS; ++s) om = max(om, ov[s]);          // entries past V hold -inf
+        part = bits_value(om);
     } else {
 #pragma unroll 8
         for (int s = 0; s < ns_mem; ++s) {
@@ -164,7 +198,7 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
     part = 0.f;
     if constexpr (NS > 0) {
 #pragma unroll
-        for (int s = 0; s < NS; ++s) part += __expf(lv[s] - mx);   // exp(-inf) = 0
+        for (int s = 0; s < NS; ++s) part += __expf(bits_value(ov[s]) - mx);   // exp(-inf) = 0
     } else {
 #pragma unroll 8
         for (int s = 0; s < ns_mem; ++s) {
@@ -196,12 +230,7 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
     {
         unsigned long long mine = 0;
         if constexpr (NS > 0) {
-#pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                const int v = idx_of(s);
-                const unsigned long long k = v < V ? order_key(lv[s], v) : 0ull;
-                mine = k > mine ? k : mine;
-            }
+            mine = thread_best(0ull);
         } else {
 #pragma unroll 8
             for (int s = 0; s < ns_mem; ++s) {
@@ -229,13 +258,14 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
         __syncthreads();
         const unsigned long long thr = s_thr;
         if constexpr (NS > 0) {
+            const uint32_t thr_hi = static_cast<uint32_t>(thr >> 32), thr_lo = static_cast<uint32_t>(thr);
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 const int v = idx_of(s);
-                const unsigned long long k = v < V ? order_key(lv[s], v) : 0ull;
-                if (k != 0 && k >= thr) {
+                const uint32_t o = ov[s], lo = 0xFFFFFFFFu - static_cast<uint32_t>(v);
+                if (v < V && (o > thr_hi || (o == thr_hi && lo >= thr_lo))) {       // key >= threshold
                     const int pos = atomicAdd(&s_ncand, 1);
-                    if (pos < kCandCap) s_cand[pos] = k;
+                    if (pos < kCandCap) s_cand[pos] = make_key(o, v);
                 }
             }
         } else {
@@ -266,16 +296,9 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
     unsigned long long taken = 0;                       // NS > 0: bit s = entry s was taken
     int ntaken = 0;                                     // NS == 0: length of s_taken
     auto local_best = [&]() -> unsigned long long {
-        unsigned long long best = 0;                    // 0 = nothing left (a real key has bit 63 or 31.. set)
+        unsigned long long best = 0;                    // 0 = nothing left
         if constexpr (NS > 0) {
-#pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                const int v = idx_of(s);
-                if (v < V && !((taken >> s) & 1ull)) {
-                    const unsigned long long k = order_key(lv[s], v);
-                    best = k > best ? k : best;
-                }
-            }
+            best = thread_best(taken);
         } else {
             for (int s = 0; s < ns_mem; ++s) {
                 const int v = tid + kThreadsDT * s;
@@ -308,19 +331,12 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
             __syncthreads();
         }
         if (mine == win) {                              // exactly one thread: tokens are distinct
-            float val;
             if constexpr (NS > 0) {
-                val = 0.f;
 #pragma unroll
                 for (int s = 0; s < NS; ++s)
-                    if (idx_of(s) == v) {
-                        val = lv[s];
-                        taken |= 1ull << s;
-                    }
-            } else {
-                val = Lane16<T>::one(row + v);
+                    if (idx_of(s) == v) taken |= 1ull << s;
             }
-            emit(k, order_key(val, v));
+            emit(k, win);
             mine = local_best();
         }
     }

@@ -337,6 +337,7 @@ __global__ __launch_bounds__(kCompactThreads) void kv_compact_kernel(
     for (int c = 0; c < kCompactChunksPerThread; ++c) {
         const int idx = tid + c * kCompactThreads;
         dst_off[c] = -1;
+        regs[c] = uint4{0u, 0u, 0u, 0u};
         if (idx < total) {
             const int j = idx / row_chunks, ch = idx - j * row_chunks;
             const int a = path[b * path_cap + j];

@@ -154,3 +154,84 @@ def test_verify_step_c5_paged(sv, oracle):
             expect_v[:, db, :, do] = v_before[:, sb, :, so]
     assert torch.equal(kd.view(torch.int16), expect_k.view(torch.int16))
     assert torch.equal(vd.view(torch.int16), expect_v.view(torch.int16))
+
+
+def test_whole_step_graph_replay_c3(sv, oracle):
+    """The step bench.py times, as it times it: one HIP graph of 32 attention layers (shared
+    workspace), argmax + acceptance in one launch and the compaction, replayed three times.
+    Layers 0 and 17 carry the seeded inputs and are compared with the oracle after every replay
+    (attention element-wise, the walk and the compacted caches bit for bit)."""
+    from gpu_util import assert_attn_close, i32, to_dev, to_host_bits, to_host_f64
+    cfg = W.CONFIGS["C3"]
+    tb = W.make_trees(cfg)
+    P = W.prefix_lengths(cfg)
+    cap = cfg.depth + 1
+    sampled = (0, 17)
+    lays = {l: W.make_attn_layer(cfg, l) for l in sampled}
+    S_cap = lays[0].k.shape[2]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(W.config_seed(cfg, 0, stream=9))
+    q = torch.randn((cfg.L, cfg.B, cfg.N, cfg.H, cfg.D), device="cuda", generator=gen).to(torch.bfloat16)
+    k = torch.randn((cfg.L, cfg.B, cfg.H, S_cap, cfg.D), device="cuda", generator=gen).to(torch.bfloat16)
+    v = torch.randn((cfg.L, cfg.B, cfg.H, S_cap, cfg.D), device="cuda", generator=gen).to(torch.bfloat16)
+    for l in sampled:
+        q[l] = to_dev(lays[l].q)
+    out = torch.zeros_like(q)
+    Pd, par, dtok, logits = i32(P), i32(tb.parent), i32(tb.draft_tok), to_dev(tb.logits)
+    desc = sv.binding.make_attn_desc(q[0], k[0], out[0])
+    workspace = torch.zeros(max(sv.specvlm_tree_verify_attn_workspace_bytes(desc), 256), dtype=torch.uint8, device="cuda")
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    counters = torch.zeros(cfg.B, dtype=torch.int32, device="cuda")
+    amax = torch.zeros((cfg.B, cfg.N), dtype=torch.int32, device="cuda")
+    acc = (torch.zeros(cfg.B, dtype=torch.int32, device="cuda"), torch.zeros((cfg.B, cap), dtype=torch.int32, device="cuda"),
+           torch.zeros(cfg.B, dtype=torch.int32, device="cuda"), torch.zeros((cfg.B, cap), dtype=torch.int32, device="cuda"))
+    newp = torch.zeros(cfg.B, dtype=torch.int32, device="cuda")
+    moved = torch.zeros((cfg.B, cap, 2), dtype=torch.int32, device="cuda")
+
+    def step():
+        for l in range(cfg.L):
+            sv.specvlm_tree_verify_attn(q[l], k[l], v[l], Pd, par, out=out[l], workspace=workspace, err_flag=err, desc=desc)
+        sv.specvlm_node_argmax_accept(logits, par, dtok, counters=counters, amax=amax, err_flag=err, out=acc)
+        sv.specvlm_kv_compact(k, v, Pd, acc[1], acc[0], new_prefix_len=newp, moved_idx=moved)
+
+    def restore():
+        for l in sampled:
+            k[l] = to_dev(lays[l].k)
+            v[l] = to_dev(lays[l].v)
+
+    restore()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                           # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+
+    r_amax = oracle.node_argmax(tb.logits)
+    r_m, r_path, r_bonus, r_comm = oracle.tree_accept(tb.parent, tb.draft_tok, r_amax, path_cap=cap)
+    refs = {}
+    for l in sampled:
+        ref_o, _ = oracle.tree_attn(lays[l].q, lays[l].k, lays[l].v, P, tb.parent)
+        kk, vv = lays[l].k[None].copy(), lays[l].v[None].copy()
+        r_newp, r_moved = oracle.kv_compact(kk, vv, P, r_path, r_m)
+        refs[l] = (ref_o, kk[0], vv[0])
+    for rep in range(3):
+        restore()
+        out.zero_()
+        for t in acc:
+            t.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(err.item()) == 0 and int(counters.sum().item()) == 0
+        assert np.array_equal(amax.cpu().numpy(), r_amax), f"replay {rep}"
+        assert np.array_equal(acc[0].cpu().numpy(), r_m) and np.array_equal(acc[1].cpu().numpy(), r_path)
+        assert np.array_equal(acc[2].cpu().numpy(), r_bonus) and np.array_equal(acc[3].cpu().numpy(), r_comm)
+        assert np.array_equal(newp.cpu().numpy(), r_newp) and np.array_equal(moved.cpu().numpy(), r_moved)
+        for l in sampled:
+            ref_o, ref_k, ref_v = refs[l]
+            assert_attn_close(to_host_f64(out[l]), ref_o, "bf16", f"replay {rep} layer {l}")
+            assert np.array_equal(to_host_bits(k[l]), ref_k) and np.array_equal(to_host_bits(v[l]), ref_v), f"replay {rep}"
