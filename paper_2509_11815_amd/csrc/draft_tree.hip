@@ -43,6 +43,47 @@ struct Lane16<float> {
     __device__ static float one(const float* p) { return *p; }
 };
 
+// NS entries of a row in a thread's registers, as loaded: bf16 entries stay packed two to a
+// register and are widened where they are used (one shift or mask).
+template <typename T, int NS>
+struct RowRegs;
+template <int NS>
+struct RowRegs<uint16_t, NS> {
+    uint32_t w[NS / 2];
+    __device__ __forceinline__ float get(int s) const {
+        const uint32_t x = w[s >> 1];
+        return __uint_as_float((s & 1) ? (x & 0xFFFF0000u) : (x << 16));
+    }
+    __device__ __forceinline__ void put_vec(int j, const uint4& x) {          // entries 8j .. 8j+7
+        w[4 * j] = x.x; w[4 * j + 1] = x.y; w[4 * j + 2] = x.z; w[4 * j + 3] = x.w;
+    }
+    __device__ __forceinline__ void fill_vec(int j) {                         // -inf
+        w[4 * j] = w[4 * j + 1] = w[4 * j + 2] = w[4 * j + 3] = 0xFF80FF80u;
+    }
+    // Called between two passes over the entries: the compiler then widens the entries again in
+    // the next pass instead of keeping NS widened copies alive beside the packed ones.
+    __device__ __forceinline__ void repack() {
+#pragma unroll
+        for (int i = 0; i < NS / 2; ++i) asm volatile("" : "+v"(w[i]));
+    }
+    __device__ __forceinline__ void put_one(int s, const uint16_t* p) {       // p == nullptr: -inf; even s first
+        const uint32_t b = p ? *p : 0xFF80u;
+        w[s >> 1] = (s & 1) ? (w[s >> 1] | (b << 16)) : b;
+    }
+};
+template <int NS>
+struct RowRegs<float, NS> {
+    float f[NS];
+    __device__ __forceinline__ float get(int s) const { return f[s]; }
+    __device__ __forceinline__ void put_vec(int j, const uint4& x) {          // entries 4j .. 4j+3
+        f[4 * j] = __uint_as_float(x.x); f[4 * j + 1] = __uint_as_float(x.y);
+        f[4 * j + 2] = __uint_as_float(x.z); f[4 * j + 3] = __uint_as_float(x.w);
+    }
+    __device__ __forceinline__ void fill_vec(int j) { f[4 * j] = f[4 * j + 1] = f[4 * j + 2] = f[4 * j + 3] = -INFINITY; }
+    __device__ __forceinline__ void repack() {}
+    __device__ __forceinline__ void put_one(int s, const float* p) { f[s] = p ? *p : -INFINITY; }
+};
+
 // (logit, token) as one unsigned key whose order is "greater logit, then lower token".
 // -0 and +0 are the same real number and must tie: adding +0 turns -0 into +0.
 __device__ __forceinline__ unsigned long long order_key(float v, int idx) {
@@ -51,22 +92,10 @@ __device__ __forceinline__ unsigned long long order_key(float v, int idx) {
     return (static_cast<unsigned long long>(u) << 32) | (0xFFFFFFFFu - static_cast<uint32_t>(idx));
 }
 
-// The upper word of an order_key on its own (greater logit <=> greater word), and its inverse.
-__device__ __forceinline__ uint32_t order_bits(float v) {
-    const uint32_t u = __float_as_uint(v + 0.0f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-__device__ __forceinline__ float bits_value(uint32_t u) {
-    return __uint_as_float((u & 0x80000000u) ? (u & 0x7FFFFFFFu) : ~u);
-}
-
-__device__ __forceinline__ unsigned long long make_key(uint32_t bits, int idx) {
-    return (static_cast<unsigned long long>(bits) << 32) | (0xFFFFFFFFu - static_cast<uint32_t>(idx));
-}
-
 __device__ __forceinline__ float key_value(unsigned long long k) {     // the logit inside an order_key
-    return bits_value(static_cast<uint32_t>(k >> 32));
+    uint32_t u = static_cast<uint32_t>(k >> 32);
+    u = (u & 0x80000000u) ? (u & 0x7FFFFFFFu) : ~u;
+    return __uint_as_float(u);
 }
 
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x) {
@@ -135,58 +164,49 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
     auto idx_of = [&](int s) -> int {
         return vec ? (tid + kThreadsDT * (s / VEC)) * VEC + s % VEC : tid + kThreadsDT * s;
     };
-    // An entry is kept as the upper word of its order_key (one register; the lower word follows
-    // from the entry's position): 16 wavefronts leave a thread 128 registers, and 64-bit keys of
-    // all entries do not fit beside the entries themselves.  Entries past V hold the word of -inf.
-    uint32_t ov[NS > 0 ? NS : 1];
-    const uint32_t kNegInfBits = 0x007FFFFFu;             // order_bits(-inf)
+    // Entries are compared as floats inside a thread (no logit is NaN, and -0 == +0 as the order
+    // demands); a 64-bit key is built only for the few entries that leave the thread.  16
+    // wavefronts leave a thread 128 registers: the keys of all entries would not fit beside
+    // the entries.  Entries past V hold -inf.
+    RowRegs<T, (NS > 0 ? NS : 8)> lv;
     if constexpr (NS > 0) {
         if (vec) {
 #pragma unroll
             for (int j = 0; j < NS / VEC; ++j) {
                 const int v0 = (tid + kThreadsDT * j) * VEC;
-                if (v0 < V) {
-                    const uint4 x = *reinterpret_cast<const uint4*>(row + v0);
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) ov[j * VEC + e] = order_bits(Lane16<T>::at(x, e));
-                } else {
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) ov[j * VEC + e] = kNegInfBits;
-                }
+                if (v0 < V) lv.put_vec(j, *reinterpret_cast<const uint4*>(row + v0));
+                else lv.fill_vec(j);
             }
         } else {
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 const int v = tid + kThreadsDT * s;
-                ov[s] = v < V ? order_bits(Lane16<T>::one(row + v)) : kNegInfBits;
+                lv.put_one(s, v < V ? row + v : nullptr);
             }
         }
     }
     // Best entry of this thread among those not in `skip` (bit s = entry s): its key, or 0 when
     // none is left.  A thread's entries are in ascending token order, so "greater" alone keeps
-    // the lowest token among equal logits.  (A key is never 0: no logit is NaN.)
-    auto thread_best = [&](unsigned long long skip) -> unsigned long long {
-        uint32_t bo = 0;
-        int bv = 0;
+    // the lowest token among equal logits.
+    auto thread_best = [&](unsigned long long skip) __attribute__((always_inline)) -> unsigned long long {
+        float bf = 0.f;
+        int bv = -1;
         if constexpr (NS > 0) {
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 const int v = idx_of(s);
-                const uint32_t o = (v < V && !((skip >> s) & 1ull)) ? ov[s] : 0u;
-                if (o > bo) { bo = o; bv = v; }
+                if (v < V && !((skip >> s) & 1ull) && (bv < 0 || lv.get(s) > bf)) { bf = lv.get(s); bv = v; }
             }
         }
-        return bo ? make_key(bo, bv) : 0ull;
+        return bv >= 0 ? order_key(bf, bv) : 0ull;
     };
     const int ns_mem = (V + kThreadsDT - 1) / kThreadsDT;          // NS == 0: entries per thread
 
     // ---- log-sum-exp of the row -----------------------------------------------------------
     float part = -INFINITY;
     if constexpr (NS > 0) {
-        uint32_t om = 0;
 #pragma unroll
-        for (int s = 0; s < NS; ++s) om = max(om, ov[s]);          // entries past V hold -inf
-        part = bits_value(om);
+        for (int s = 0; s < NS; ++s) part = fmaxf(part, lv.get(s));    // entries past V hold -inf
     } else {
 #pragma unroll 8
         for (int s = 0; s < ns_mem; ++s) {
@@ -194,11 +214,13 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
             if (v < V) part = fmaxf(part, Lane16<T>::one(row + v));
         }
     }
+    const float tmax = part;                            // NS > 0: this thread's greatest logit
     const float mx = wg_max(part, s_red);
+    lv.repack();
     part = 0.f;
     if constexpr (NS > 0) {
 #pragma unroll
-        for (int s = 0; s < NS; ++s) part += __expf(bits_value(ov[s]) - mx);   // exp(-inf) = 0
+        for (int s = 0; s < NS; ++s) part += __expf(lv.get(s) - mx);   // exp(-inf) = 0
     } else {
 #pragma unroll 8
         for (int s = 0; s < ns_mem; ++s) {
@@ -207,6 +229,7 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
         }
     }
     const float Z = wg_sum(part, s_red);
+    lv.repack();
     const float lse = mx + logf(Z);
     const float c = cum ? cum[b * cum_stride_b + w] : 0.f;
     const int par = parent_idx ? parent_idx[b * parent_stride_b + w] : -1;
@@ -230,7 +253,12 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
     {
         unsigned long long mine = 0;
         if constexpr (NS > 0) {
-            mine = thread_best(0ull);
+            // the first entry that equals the thread's maximum (found for the log-sum-exp above)
+            int bs = NS;
+#pragma unroll
+            for (int s = NS - 1; s >= 0; --s) bs = lv.get(s) == tmax ? s : bs;
+            const int bv = idx_of(bs);
+            mine = bv < V ? order_key(tmax, bv) : 0ull;   // a thread whose entries all lie past V has none
         } else {
 #pragma unroll 8
             for (int s = 0; s < ns_mem; ++s) {
@@ -257,15 +285,20 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
         }                                               // than K groups hold an entry: the threshold stays 0
         __syncthreads();
         const unsigned long long thr = s_thr;
+        lv.repack();
         if constexpr (NS > 0) {
-            const uint32_t thr_hi = static_cast<uint32_t>(thr >> 32), thr_lo = static_cast<uint32_t>(thr);
+            // Entries whose logit reaches the threshold's logit: a superset of the entries whose
+            // key reaches the threshold (it adds higher tokens with the same logit), which the
+            // ranking below does not mind.  Only a thread whose maximum reaches it has any.
+            const float thr_val = thr ? key_value(thr) : -INFINITY;
+            if (tmax >= thr_val) {
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                const int v = idx_of(s);
-                const uint32_t o = ov[s], lo = 0xFFFFFFFFu - static_cast<uint32_t>(v);
-                if (v < V && (o > thr_hi || (o == thr_hi && lo >= thr_lo))) {       // key >= threshold
-                    const int pos = atomicAdd(&s_ncand, 1);
-                    if (pos < kCandCap) s_cand[pos] = make_key(o, v);
+                for (int s = 0; s < NS; ++s) {
+                    const int v = idx_of(s);
+                    if (lv.get(s) >= thr_val && v < V) {
+                        const int pos = atomicAdd(&s_ncand, 1);
+                        if (pos < kCandCap) s_cand[pos] = order_key(lv.get(s), v);
+                    }
                 }
             }
         } else {
@@ -295,7 +328,7 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
     // ---- K rounds of arg-max (any input) --------------------------------------------------------
     unsigned long long taken = 0;                       // NS > 0: bit s = entry s was taken
     int ntaken = 0;                                     // NS == 0: length of s_taken
-    auto local_best = [&]() -> unsigned long long {
+    auto local_best = [&]() __attribute__((always_inline)) -> unsigned long long {
         unsigned long long best = 0;                    // 0 = nothing left
         if constexpr (NS > 0) {
             best = thread_best(taken);
