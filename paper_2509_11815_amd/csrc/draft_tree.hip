@@ -377,35 +377,51 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
 
 // ---------------------------------------------------------------------------------------
 // Ranking of scored candidates: candidate i beats j when score[i] > score[j], or the scores
-// are equal and i < j.  rank(i) = number of candidates that beat i; the M winners are the
-// candidates of rank < M; a winner's position is the number of winners of lower index.
-// s_sc holds the c scores, s_pos (c ints) receives the position of a winner and -1 otherwise.
+// are equal and i < j -- i.e. when its order_key(score, index) is the greater one.  rank(i) =
+// number of candidates that beat i; the M winners are the candidates of rank < M; a winner's
+// position is the number of winners of lower index.
+// s_key holds the c keys (16-byte aligned).  On return the low word of s_key[i] holds candidate
+// i's position among the winners, or -1 (pos_of below); the keys are gone.
+// All c*c comparisons run on one compute unit, so what counts is instructions per comparison:
+// one 64-bit compare and one add-with-carry, two keys per LDS read.  With few candidates
+// several threads share a candidate (each takes a slice of the others) so that every
+// wavefront has work.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ void rank_winners(const float* s_sc, int* s_pos, int c, int M) {
+__device__ __forceinline__ int pos_of(const unsigned long long* s_key, int i) {
+    return reinterpret_cast<const int*>(s_key)[2 * i];
+}
+
+__device__ __forceinline__ void rank_winners(unsigned long long* s_key, int c, int M) {
     __shared__ int s_wcount[kWavesDT];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c4 = c & ~3;
-    int base = 0;                                          // winners among candidates below this pass
-    for (int i0 = 0; i0 < c; i0 += kThreadsDT) {           // uniform trip count
-        const int i = i0 + tid;
-        bool win = false;
-        if (i < c) {
-            const float si = s_sc[i];
-            int beaten = 0;
-            for (int j = 0; j < c4; j += 4) {              // scores sit 16-byte aligned in LDS
-                const float4 q = *reinterpret_cast<const float4*>(s_sc + j);
-                beaten += (q.x > si || (q.x == si && j < i)) ? 1 : 0;
-                beaten += (q.y > si || (q.y == si && j + 1 < i)) ? 1 : 0;
-                beaten += (q.z > si || (q.z == si && j + 2 < i)) ? 1 : 0;
-                beaten += (q.w > si || (q.w == si && j + 3 < i)) ? 1 : 0;
-            }
-            for (int j = c4; j < c; ++j) {
-                const float sj = s_sc[j];
-                beaten += (sj > si || (sj == si && j < i)) ? 1 : 0;
-            }
-            win = beaten < M;
+    int parts = 1, shift = 0;                              // threads per candidate (uniform)
+    while (parts < 16 && c * (parts * 2) <= kThreadsDT) { parts *= 2; ++shift; }
+    const int per_pass = kThreadsDT >> shift;              // candidates per pass
+    const int per = ((c + parts - 1) / parts + 1) & ~1;    // others per thread, even: slices start 16-byte aligned
+    const int part = tid & (parts - 1), slot = tid >> shift;
+    const int j0 = part * per, j1 = min(j0 + per, c);
+    unsigned winbits = 0;                                  // bit p: this thread's candidate of pass p won (at most 8 passes)
+    int pass = 0;
+    for (int i0 = 0; i0 < c; i0 += per_pass, ++pass) {     // uniform trip count
+        const int i = i0 + slot;
+        const unsigned long long ki = i < c ? s_key[i] : ~0ull;
+        int beaten = 0, j = j0;
+        for (; j + 1 < j1; j += 2) {
+            const ulonglong2 q = *reinterpret_cast<const ulonglong2*>(s_key + j);
+            beaten += q.x > ki ? 1 : 0;
+            beaten += q.y > ki ? 1 : 0;
         }
-        // position of a winner = winners of lower index: earlier passes, earlier wavefronts, lower lanes
+        if (j < j1) beaten += s_key[j] > ki ? 1 : 0;
+        for (int off = 1; off < parts; off <<= 1) beaten += __shfl_xor(beaten, off);
+        if (i < c && part == 0 && beaten < M) winbits |= 1u << pass;
+    }
+    __syncthreads();                                       // the keys have been read for the last time
+    // position of a winner = winners of lower index: earlier passes, earlier wavefronts, lower lanes
+    int base = 0;
+    pass = 0;
+    for (int i0 = 0; i0 < c; i0 += per_pass, ++pass) {
+        const int i = i0 + slot;
+        const bool win = (winbits >> pass) & 1u;
         const unsigned long long bal = __ballot(win);
         if (lane == 0) s_wcount[wave] = __popcll(bal);
         __syncthreads();
@@ -416,7 +432,8 @@ __device__ __forceinline__ void rank_winners(const float* s_sc, int* s_pos, int 
             before += x < wave ? n : 0;
             total += n;
         }
-        if (i < c) s_pos[i] = win ? before + __popcll(bal & ((1ull << lane) - 1ull)) : -1;
+        if (i < c && part == 0)
+            reinterpret_cast<int*>(s_key)[2 * i] = win ? before + __popcll(bal & ((1ull << lane) - 1ull)) : -1;
         base += total;
         __syncthreads();                                   // s_wcount is rewritten by the next pass
     }
@@ -427,19 +444,18 @@ __global__ __launch_bounds__(kThreadsDT) void draft_select_kernel(
     int index_base, int32_t* __restrict__ sel_out, float* __restrict__ sel_score_out,
     int32_t* __restrict__ count_out) {
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
-    float* s_sc = reinterpret_cast<float*>(s_dyn);
-    int* s_pos = reinterpret_cast<int*>(s_dyn) + C;
+    unsigned long long* s_key = reinterpret_cast<unsigned long long*>(s_dyn);
     const int b = blockIdx.x, tid = threadIdx.x;
     const int c = num_cand ? min(max(num_cand[b], 0), C) : C;
-    for (int i = tid; i < c; i += kThreadsDT) s_sc[i] = score[b * score_stride_b + i];
+    for (int i = tid; i < c; i += kThreadsDT) s_key[i] = order_key(score[b * score_stride_b + i], i);
     __syncthreads();
-    rank_winners(s_sc, s_pos, c, M);
+    rank_winners(s_key, c, M);
     const int count = min(M, c);
     for (int i = tid; i < c; i += kThreadsDT) {
-        const int p = s_pos[i];
+        const int p = pos_of(s_key, i);
         if (p >= 0) {
             sel_out[b * M + p] = i + index_base;
-            if (sel_score_out) sel_score_out[b * M + p] = s_sc[i];
+            if (sel_score_out) sel_score_out[b * M + p] = score[b * score_stride_b + i];
         }
     }
     for (int p = count + tid; p < M; p += kThreadsDT) {
@@ -455,8 +471,7 @@ __global__ __launch_bounds__(kThreadsDT) void draft_finalize_kernel(
     const int32_t* __restrict__ root_token, int32_t* __restrict__ parent_out, int32_t* __restrict__ draft_tok_out,
     int32_t* __restrict__ node_cand_out, int32_t* __restrict__ num_nodes_out, int32_t* __restrict__ err_flag) {
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
-    float* s_sc = reinterpret_cast<float*>(s_dyn);
-    int* s_pos = reinterpret_cast<int*>(s_dyn) + C;
+    unsigned long long* s_key = reinterpret_cast<unsigned long long*>(s_dyn);
     const int b = blockIdx.x, tid = threadIdx.x;
     int err = 0;
     int c = num_cand ? num_cand[b] : C;
@@ -466,12 +481,12 @@ __global__ __launch_bounds__(kThreadsDT) void draft_finalize_kernel(
     }
     const int M = N_max - 1;
     const int64_t base = b * cand_stride_b;
-    for (int i = tid; i < c; i += kThreadsDT) s_sc[i] = cand_score[base + i];
+    for (int i = tid; i < c; i += kThreadsDT) s_key[i] = order_key(cand_score[base + i], i);
     __syncthreads();
-    rank_winners(s_sc, s_pos, c, M);
+    rank_winners(s_key, c, M);
     const int count = min(M, c);
     for (int i = tid; i < c; i += kThreadsDT) {
-        const int p = s_pos[i];
+        const int p = pos_of(s_key, i);
         if (p < 0) continue;
         const int cp = cand_parent[base + i];
         int pn = -1;
@@ -479,10 +494,10 @@ __global__ __launch_bounds__(kThreadsDT) void draft_finalize_kernel(
             err |= SPECVLM_ERR_BAD_PARENT;
         } else if (cp < 0) {
             pn = 0;
-        } else if (s_pos[cp] < 0) {
+        } else if (pos_of(s_key, cp) < 0) {
             err |= SPECVLM_ERR_TREE_NOT_CLOSED;         // a chosen candidate whose parent was not chosen
         } else {
-            pn = s_pos[cp] + 1;
+            pn = pos_of(s_key, cp) + 1;
         }
         const int node = p + 1;
         parent_out[b * N_max + node] = pn;
