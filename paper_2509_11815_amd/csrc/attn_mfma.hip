@@ -29,9 +29,10 @@
 //   softmax   online (running max / sum per query) in fp32 on the S^T fragments: a lane
 //             holds one query and 8 keys, so row statistics need two cross-lane steps, and
 //             exp2(S^T) packed to bf16 is already the B operand of the next MFMA
-//   PV        O^T[D x 64 q] += V^T . P^T; V rows are read from LDS as rows and transposed
-//             two bytes at a time with v_perm_b32 (the contraction index may be permuted
-//             freely, so an operand's "8 consecutive k" are 8 rows of one column)
+//   PV        O^T[D x 64 q] += V^T . P^T; the V^T operand comes out of LDS transposed
+//             (ds_read_b64_tr_b16 on V tiles swizzled in 32-byte chunks; the contraction
+//             index may be permuted freely, so an operand's "8 consecutive k" are the 8
+//             keys whose probabilities the lane already holds)
 //   masks     prefix keys need none; only tiles touching the tree region or the request's
 //             end test the per-query ancestor bit mask (select, never multiply)
 //   merge     the streams of a workgroup are merged through LDS (one round, the rings are
@@ -50,6 +51,15 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+// ds_read_b64_tr_b16: inside a block of 16 lanes, lane i receives element i % 4 of the four
+// 8-byte rows whose addresses lanes i/4, i/4 + 4, i/4 + 8 and i/4 + 12 pass.
+__device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* generic_lds_addr) {
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)generic_lds_addr);
+}
 
 constexpr int kWaves = 8;           // wavefronts per workgroup: two per SIMD
 constexpr int kShare = 4;           // wavefronts sharing one key stream, 64/kShare query rows each
@@ -136,22 +146,27 @@ __device__ __forceinline__ void store16_coherent(void* dst, u32x4 v) {
     asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(dst), "v"(v) : "memory");
 }
 
-// Writes one wavefront's 16 query rows: out[t][i] = O^T[d = NT*(4g+i) + t][q], unnormalised.
+// Writes one wavefront's 16 query rows: out[t][i] = O^T[d = 16t + 4g + i][q], unnormalised.
 template <int NT>
 __device__ __forceinline__ void store_rows(const MfmaParams& p, const f32x4 (&out)[NT], float M, float L,
                                            int b, int h, int qi, int g, int n) {
     if (qi >= n) return;
     const float inv = 1.f / L;
-    uint16_t* orow = p.o + b * p.o_sb + qi * p.o_sn + h * p.o_sh + 4 * NT * g;
+    // A lane holds 4 consecutive head dims per block t.  Lanes g = 2v and 2v+1 of a query row
+    // trade halves so that each stores 8 consecutive dims (16 bytes): the even lane keeps the
+    // even blocks, the odd lane the odd ones.
+    const bool odd = g & 1;
+    uint16_t* orow = p.o + b * p.o_sb + qi * p.o_sn + h * p.o_sh + 4 * (g & ~1);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        uint32_t w[NT / 2];
-#pragma unroll
-        for (int t = 0; t < NT; t += 2) w[t / 2] = pack_bf16x2(out[t][i] * inv, out[t + 1][i] * inv);
-        if constexpr (NT == 8)
-            *reinterpret_cast<u32x4*>(orow + i * NT) = u32x4{w[0], w[1], w[2], w[3]};
-        else
-            *reinterpret_cast<u32x2*>(orow + i * NT) = u32x2{w[0], w[1]};
+    for (int u = 0; u < NT / 2; ++u) {
+        const uint32_t e0 = pack_bf16x2(out[2 * u][0] * inv, out[2 * u][1] * inv);
+        const uint32_t e1 = pack_bf16x2(out[2 * u][2] * inv, out[2 * u][3] * inv);
+        const uint32_t o0 = pack_bf16x2(out[2 * u + 1][0] * inv, out[2 * u + 1][1] * inv);
+        const uint32_t o1 = pack_bf16x2(out[2 * u + 1][2] * inv, out[2 * u + 1][3] * inv);
+        const uint32_t r0 = __shfl_xor(odd ? e0 : o0, 16);     // the partner's share of the block this lane keeps
+        const uint32_t r1 = __shfl_xor(odd ? e1 : o1, 16);
+        const u32x4 w = odd ? u32x4{r0, r1, o0, o1} : u32x4{e0, e1, r0, r1};
+        *reinterpret_cast<u32x4*>(orow + 16 * (2 * u + (odd ? 1 : 0))) = w;
     }
     if (p.lse && g == 0)
         p.lse[(static_cast<int64_t>(b) * p.H_q + h) * p.N_max + qi] = M * p.scale + __log2f(L) * kLn2;
@@ -238,7 +253,15 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
 #pragma unroll
     for (int ii = 0; ii < KPW; ++ii)
         voff_k[ii] = lrow * row_bytes + (lpos ^ (((qw * KPW + ii) * RPI + lrow) & (ROWG - 1))) * 16;
-    const uint32_t voff_v = lrow * row_bytes + lpos * 16;
+    // V tiles land swizzled in 32-byte chunks (16 head dims): chunk c of key row r sits at chunk
+    // position c ^ vswz(r), so that the transposing reads of the PV product, which take 32 bytes
+    // from each of 8 different rows per half wavefront, hit every LDS bank once.
+    auto vswz = [](int r) { return D == 128 ? (r & 7) : ((r >> 1) & 3); };
+    auto vgran = [&](int r) { return (((lpos >> 1) ^ vswz(r)) << 1) | (lpos & 1); };   // granule this lane fetches for row r
+    uint32_t voff_v[KPW];
+#pragma unroll
+    for (int ii = 0; ii < KPW; ++ii)
+        voff_v[ii] = lrow * row_bytes + vgran((qw * KPW + ii) * RPI + lrow) * 16;
     // Paged cache: physical ids of the two 16-key blocks of a tile, through the scalar cache.
     // They are looked up one tile ahead of the loads that need them, so the look-up latency
     // never sits between a free ring slot and its refill.
@@ -260,12 +283,12 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         for (int ii = 0; ii < KPW; ++ii) {
             const int i = qw * KPW + ii;
             int r0 = lo + i * RPI;                         // uniform: first row of the group
-            uint32_t vk = voff_k[ii], vv = voff_v;
+            uint32_t vk = voff_k[ii], vv = voff_v[ii];
             if (r0 + RPI > lim) {                          // uniform, rare: some row of the group is not real
                 r0 = min(r0, ((lim - 1) / RPI) * RPI);     // the last group with a real row
                 const uint32_t rl = min(lrow, lim - 1 - r0) * row_bytes;
                 vk = rl + (lpos ^ ((i * RPI + lrow) & (ROWG - 1))) * 16;
-                vv = rl + lpos * 16;
+                vv = rl + vgran(i * RPI + lrow) * 16;
             }
             int64_t base = head_off;                       // elements, uniform
             if (p.g.block_table) {
@@ -454,30 +477,27 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
             for (int x = 0; x < 4; ++x) w[x] = pack_bf16x2(pr[2 * x], pr[2 * x + 1]);
             pf[qb] = __builtin_bit_cast(bf16x8, w);
         }
-        // O^T += V^T P^T: contraction slot 8g + jj <-> key 16*(jj/4) + 4g + jj%4 of the tile
-        uint32_t vr[8][NT / 2];
+        // O^T += V^T P^T: contraction slot 8g + jj <-> key 16*(jj/4) + 4g + jj%4 of the tile.
+        // A operand of head-dim block t: lane (l16, g) needs V[those 8 keys][d = 16t + l16].  A
+        // transposing LDS read hands lane i of a 16-lane block element i%4 of the 8-byte rows
+        // whose addresses lanes i/4, i/4+4, i/4+8, i/4+12 supply: with lane j supplying key
+        // kb + j/4, dims 16t + 4(j%4) .. +3, lane i receives keys kb .. kb+3 at dim 16t + i --
+        // one read for kb = 4g (slots 0-3), one for kb = 16 + 4g (slots 4-7).
+        {
+            const int jk = l16 >> 2, jd = l16 & 3;
+            const int k0 = 4 * g + jk, k1 = 16 + 4 * g + jk;
+            const unsigned char* r0 = vt + k0 * (ROWG * 16) + jd * 8;
+            const unsigned char* r1 = vt + k1 * (ROWG * 16) + jd * 8;
+            const int s0 = vswz(k0), s1 = vswz(k1);
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-            const int r = (jj >> 2) * 16 + 4 * g + (jj & 3);
-            if constexpr (NT == 8) {
-                const u32x4 w = *reinterpret_cast<const u32x4*>(vt + (r * ROWG + l16) * 16);
-                vr[jj][0] = w[0]; vr[jj][1] = w[1]; vr[jj][2] = w[2]; vr[jj][3] = w[3];
-            } else {
-                const u32x2 w = *reinterpret_cast<const u32x2*>(vt + r * ROWG * 16 + l16 * 8);
-                vr[jj][0] = w[0]; vr[jj][1] = w[1];
+            for (int t = 0; t < NT; ++t) {
+                const s16x4 lo = lds_read_tr16(r0 + ((t ^ s0) << 5));
+                const s16x4 hi = lds_read_tr16(r1 + ((t ^ s1) << 5));
+                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8 va = __builtin_bit_cast(bf16x8, both);
+#pragma unroll
+                for (int qb = 0; qb < QBW; ++qb) acc[qb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pf[qb], acc[qb][t], 0, 0, 0);
             }
-        }
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const uint32_t sel = (t & 1) ? 0x07060302u : 0x05040100u;
-            u32x4 w;
-            w[0] = __builtin_amdgcn_perm(vr[1][t >> 1], vr[0][t >> 1], sel);
-            w[1] = __builtin_amdgcn_perm(vr[3][t >> 1], vr[2][t >> 1], sel);
-            w[2] = __builtin_amdgcn_perm(vr[5][t >> 1], vr[4][t >> 1], sel);
-            w[3] = __builtin_amdgcn_perm(vr[7][t >> 1], vr[6][t >> 1], sel);
-            const bf16x8 va = __builtin_bit_cast(bf16x8, w);
-#pragma unroll
-            for (int qb = 0; qb < QBW; ++qb) acc[qb][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pf[qb], acc[qb][t], 0, 0, 0);
         }
         }
         // This wavefront's reads of the slot have returned (their values fed the MFMAs above) and
