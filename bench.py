@@ -211,19 +211,23 @@ def main():
            torch.empty((B, N), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev))
     root_tok = torch.zeros(B, dtype=torch.int32, device=dev)
 
+    grow_counters = torch.zeros(B, dtype=torch.int32, device=dev)
+
     def grow():
+        # a level = Top-K of the expanded nodes' rows + the choice of the nodes the next level expands, one launch
         base, count = 0, 0
         for d in range(cfg.depth):
             rows = 1 if d == 0 else K
             nb = base + count
             out = dict(score_out=c_score[:, nb:nb + rows * K], token_out=c_tok[:, nb:nb + rows * K],
                        parent_out=c_par[:, nb:nb + rows * K])
-            if d == 0:
-                sv.specvlm_draft_topk(lvl_logits[d], K, **out)
+            prev = dict(cum=sel[d][1], parent_idx=sel[d][0]) if d else {}
+            if d + 1 < cfg.depth:
+                sv.specvlm_draft_topk_select(lvl_logits[d], K, K, index_base=nb, sel_out=sel[d + 1][0],
+                                             sel_score_out=sel[d + 1][1], count_out=sel[d + 1][2],
+                                             counters=grow_counters, **prev, **out)
             else:
-                sv.specvlm_draft_select(c_score[:, base:base + count], K, index_base=base, sel_out=sel[d][0],
-                                        sel_score_out=sel[d][1], count_out=sel[d][2])
-                sv.specvlm_draft_topk(lvl_logits[d], K, cum=sel[d][1], parent_idx=sel[d][0], **out)
+                sv.specvlm_draft_topk(lvl_logits[d], K, **prev, **out)
             base, count = nb, rows * K
         sv.specvlm_draft_finalize(c_score, c_par, c_tok, root_tok, N, err_flag=err, out=fin)
 

@@ -330,6 +330,23 @@ int32_t specvlm_draft_topk(int32_t dtype, int32_t B, int32_t W, int32_t V, int32
                            int64_t out_stride_b, float *lse_out_dev, void *stream);
 
 /*
+ * specvlm_draft_topk followed by specvlm_draft_select over the level's W*K new candidates
+ * (score = score_out[b, 0 .. W*K), same M / index_base / sel_* / count_out meaning), as one
+ * launch: the workgroup that finishes a request's last row makes the selection.  W*K <= 1024.
+ *   counters_dev   device int32 [B], ZERO-FILLED ONCE after allocation (every call leaves it
+ *                  zero); calls that may run concurrently need separate counters
+ */
+int32_t specvlm_draft_topk_select(int32_t dtype, int32_t B, int32_t W, int32_t V, int32_t K,
+                                  const void *logits_dev, int64_t stride_b, int64_t stride_w,
+                                  const float *cum_dev, int64_t cum_stride_b,
+                                  const int32_t *parent_idx_dev, int64_t parent_stride_b,
+                                  float *score_out_dev, int32_t *token_out_dev, int32_t *parent_out_dev,
+                                  int64_t out_stride_b, float *lse_out_dev,
+                                  int32_t M, int32_t index_base, int32_t *sel_out_dev,
+                                  float *sel_score_out_dev, int32_t *count_out_dev,
+                                  int32_t *counters_dev, void *stream);
+
+/*
  * The M most valuable of a request's scored candidates: candidate i beats j when
  * score[i] > score[j], or the scores are equal and i < j (scores are compared as the stored fp32
  * numbers).  Winners are listed in increasing candidate index.

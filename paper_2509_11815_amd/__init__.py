@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     specvlm_draft_finalize,
     specvlm_draft_select,
     specvlm_draft_topk,
+    specvlm_draft_topk_select,
     specvlm_head_argmax,
     specvlm_head_argmax_workspace_bytes,
     specvlm_kv_compact,

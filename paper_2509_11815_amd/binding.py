@@ -20,7 +20,8 @@ ERR_BITS = {1: "BAD_PARENT", 2: "BAD_NUM_NODES", 4: "BAD_LENGTH", 8: "PATH_TOO_L
 EXPORTS = ["specvlm_version", "specvlm_last_hip_error", "specvlm_tree_verify_attn_workspace_bytes",
            "specvlm_tree_verify_attn_num_splits",
            "specvlm_tree_verify_attn", "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_tree_accept_sample",
-           "specvlm_kv_compact", "specvlm_draft_topk", "specvlm_draft_select", "specvlm_draft_finalize",
+           "specvlm_kv_compact", "specvlm_draft_topk", "specvlm_draft_topk_select", "specvlm_draft_select",
+           "specvlm_draft_finalize",
            "specvlm_head_argmax", "specvlm_head_argmax_workspace_bytes",
            "specvlm_visual_pool", "specvlm_visual_prune", "specvlm_node_argmax_accept"]
 
@@ -73,6 +74,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.specvlm_kv_compact.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, vp, i64, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     L.specvlm_draft_topk.restype = i32
     L.specvlm_draft_topk.argtypes = [i32] * 5 + [vp, i64, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp, vp]
+    L.specvlm_draft_topk_select.restype = i32
+    L.specvlm_draft_topk_select.argtypes = ([i32] * 5 + [vp, i64, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp] +
+                                            [i32, i32, vp, vp, vp, vp, vp])
     L.specvlm_draft_select.restype = i32
     L.specvlm_draft_select.argtypes = [i32, i32, i32, vp, i64, vp, i32, vp, vp, vp, vp]
     L.specvlm_draft_finalize.restype = i32
@@ -334,6 +338,47 @@ def specvlm_draft_topk(logits, K, *, cum=None, parent_idx=None, score_out=None, 
         _stream(stream))
     _check(rc, "specvlm_draft_topk")
     return score_out, token_out, parent_out
+
+
+def specvlm_draft_topk_select(logits, K, M, *, cum=None, parent_idx=None, score_out=None, token_out=None,
+                              parent_out=None, lse_out=None, index_base=0, sel_out=None, sel_score_out=None,
+                              count_out=None, counters=None, stream=None):
+    """specvlm_draft_topk and the selection of the M best of the level's W*K new candidates in one launch.
+    `counters` is an int32 [B] device tensor, zero-filled once (allocated here when omitted).
+    Returns (score_out, token_out, parent_out, sel_out, sel_score_out, count_out)."""
+    B, W, V = logits.shape
+    dev = logits.device
+    if logits.stride(2) != 1:
+        raise ValueError("vocab dimension must be contiguous")
+    if score_out is None:
+        score_out = torch.empty((B, W * K), dtype=torch.float32, device=dev)
+    if token_out is None:
+        token_out = torch.empty((B, W * K), dtype=torch.int32, device=dev)
+    if parent_out is None and parent_idx is not None:
+        parent_out = torch.empty((B, W * K), dtype=torch.int32, device=dev)
+    outs = [t for t in (score_out, token_out, parent_out) if t is not None]
+    if any(t.stride(0) != score_out.stride(0) or t.stride(1) != 1 or t.shape[1] < W * K for t in outs):
+        raise ValueError("score_out / token_out / parent_out must share one row stride and hold W*K entries")
+    if token_out.dtype != torch.int32 or (parent_out is not None and parent_out.dtype != torch.int32):
+        raise TypeError("token_out / parent_out must be int32")
+    _dev_f32(score_out, "score_out")
+    if sel_out is None:
+        sel_out = torch.empty((B, M), dtype=torch.int32, device=dev)
+    if sel_score_out is None:
+        sel_score_out = torch.empty((B, M), dtype=torch.float32, device=dev)
+    if count_out is None:
+        count_out = torch.empty(B, dtype=torch.int32, device=dev)
+    if counters is None:
+        counters = torch.zeros(B, dtype=torch.int32, device=dev)
+    rc = lib().specvlm_draft_topk_select(
+        _dtype_code(logits), B, W, V, K, _ptr(logits), logits.stride(0), logits.stride(1),
+        _ptr(_dev_f32(cum, "cum")), 0 if cum is None else cum.stride(0),
+        _ptr(parent_idx), 0 if parent_idx is None else parent_idx.stride(0),
+        _ptr(score_out), _ptr(token_out), _ptr(parent_out), score_out.stride(0), _ptr(_dev_f32(lse_out, "lse_out")),
+        M, index_base, _ptr(_dev_i32(sel_out, "sel_out")), _ptr(_dev_f32(sel_score_out, "sel_score_out")),
+        _ptr(_dev_i32(count_out, "count_out")), _ptr(_dev_i32(counters, "counters")), _stream(stream))
+    _check(rc, "specvlm_draft_topk_select")
+    return score_out, token_out, parent_out, sel_out, sel_score_out, count_out
 
 
 def specvlm_draft_select(score, M, *, num_cand=None, index_base=0, sel_out=None, sel_score_out=None,

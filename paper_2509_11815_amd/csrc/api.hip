@@ -50,7 +50,7 @@ using namespace specvlm;
 
 extern "C" {
 
-int32_t specvlm_version(void) { return 200; }
+int32_t specvlm_version(void) { return 201; }
 
 int32_t specvlm_last_hip_error(void) { return g_last_hip_error; }
 
@@ -261,7 +261,29 @@ int32_t specvlm_draft_topk(int32_t dtype, int32_t B, int32_t W, int32_t V, int32
     if (reinterpret_cast<uintptr_t>(logits_dev) % es) return SPECVLM_INVALID_ARG;
     return launch_draft_topk(dtype, B, W, V, K, logits_dev, stride_b, stride_w, cum_dev, cum_stride_b,
                              parent_idx_dev, parent_stride_b, score_out_dev, token_out_dev, parent_out_dev,
-                             out_stride_b, lse_out_dev, static_cast<hipStream_t>(stream));
+                             out_stride_b, lse_out_dev, 0, 0, nullptr, nullptr, nullptr, nullptr,
+                             static_cast<hipStream_t>(stream));
+}
+
+int32_t specvlm_draft_topk_select(int32_t dtype, int32_t B, int32_t W, int32_t V, int32_t K, const void* logits_dev,
+                                  int64_t stride_b, int64_t stride_w, const float* cum_dev, int64_t cum_stride_b,
+                                  const int32_t* parent_idx_dev, int64_t parent_stride_b, float* score_out_dev,
+                                  int32_t* token_out_dev, int32_t* parent_out_dev, int64_t out_stride_b,
+                                  float* lse_out_dev, int32_t M, int32_t index_base, int32_t* sel_out_dev,
+                                  float* sel_score_out_dev, int32_t* count_out_dev, int32_t* counters_dev,
+                                  void* stream) {
+    if (dtype != SPECVLM_BF16 && dtype != SPECVLM_F32) return SPECVLM_INVALID_ARG;
+    if (B < 1 || B > 65535 || W < 1 || V < 1 || K < 1 || K > V || K > SPECVLM_MAX_NODES) return SPECVLM_INVALID_ARG;
+    if (!logits_dev || !score_out_dev || !token_out_dev || !sel_out_dev || !counters_dev) return SPECVLM_INVALID_ARG;
+    if (stride_b < 0 || stride_w < V || cum_stride_b < 0 || parent_stride_b < 0) return SPECVLM_INVALID_ARG;
+    if (out_stride_b < static_cast<int64_t>(W) * K) return SPECVLM_INVALID_ARG;
+    if (static_cast<int64_t>(W) * K > 1024 || M < 1 || M > SPECVLM_MAX_CANDIDATES) return SPECVLM_INVALID_ARG;
+    const uintptr_t es = dtype == SPECVLM_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(logits_dev) % es) return SPECVLM_INVALID_ARG;
+    return launch_draft_topk(dtype, B, W, V, K, logits_dev, stride_b, stride_w, cum_dev, cum_stride_b,
+                             parent_idx_dev, parent_stride_b, score_out_dev, token_out_dev, parent_out_dev,
+                             out_stride_b, lse_out_dev, M, index_base, sel_out_dev, sel_score_out_dev,
+                             count_out_dev, counters_dev, static_cast<hipStream_t>(stream));
 }
 
 int32_t specvlm_draft_select(int32_t B, int32_t C, int32_t M, const float* score_dev, int64_t score_stride_b,

@@ -146,6 +146,10 @@ __device__ __forceinline__ void store16_coherent(void* dst, u32x4 v) {
     asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(dst), "v"(v) : "memory");
 }
 
+__device__ __forceinline__ void store8_coherent(void* dst, u32x2 v) {
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" : : "v"(dst), "v"(v) : "memory");
+}
+
 // Writes one wavefront's 16 query rows: out[t][i] = O^T[d = 16t + 4g + i][q], unnormalised.
 template <int NT>
 __device__ __forceinline__ void store_rows(const MfmaParams& p, const f32x4 (&out)[NT], float M, float L,
@@ -596,8 +600,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         }
         if (g == 0) {
             float* ml = p.ws_ml + ((part0 + split) * kQRows + qi) * 2;
-            __hip_atomic_store(reinterpret_cast<uint32_t*>(ml), __float_as_uint(Mq), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(reinterpret_cast<uint32_t*>(ml + 1), __float_as_uint(Lq), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            store8_coherent(ml, u32x2{__float_as_uint(Mq), __float_as_uint(Lq)});
         }
     }
     wait_vmcnt<0>();                                   // this wavefront's write-through stores have been acknowledged

@@ -87,7 +87,8 @@ int32_t launch_draft_topk(int32_t dtype, int32_t B, int32_t W, int32_t V, int32_
                           int64_t stride_b, int64_t stride_w, const float* cum, int64_t cum_stride_b,
                           const int32_t* parent_idx, int64_t parent_stride_b, float* score_out,
                           int32_t* token_out, int32_t* parent_out, int64_t out_stride_b, float* lse_out,
-                          hipStream_t stream);
+                          int32_t M, int32_t index_base, int32_t* sel_out, float* sel_score_out,
+                          int32_t* count_out, int32_t* counters, hipStream_t stream);
 
 int32_t launch_draft_select(int32_t B, int32_t C, int32_t M, const float* score, int64_t score_stride_b,
                             const int32_t* num_cand, int32_t index_base, int32_t* sel_out,

@@ -133,6 +133,70 @@ __device__ __forceinline__ float wg_sum(float x, float* s_red) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Ranking of scored candidates: candidate i beats j when score[i] > score[j], or the scores
+// are equal and i < j -- i.e. when its order_key(score, index) is the greater one.  rank(i) =
+// number of candidates that beat i; the M winners are the candidates of rank < M; a winner's
+// position is the number of winners of lower index.
+// s_key holds the c keys (16-byte aligned).  On return the low word of s_key[i] holds candidate
+// i's position among the winners, or -1 (pos_of below); the keys are gone.
+// All c*c comparisons run on one compute unit, so what counts is instructions per comparison:
+// one 64-bit compare and one add-with-carry, two keys per LDS read.  With few candidates
+// several threads share a candidate (each takes a slice of the others) so that every
+// wavefront has work.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int pos_of(const unsigned long long* s_key, int i) {
+    return reinterpret_cast<const int*>(s_key)[2 * i];
+}
+
+__device__ __forceinline__ void rank_winners(unsigned long long* s_key, int c, int M) {
+    __shared__ int s_wcount[kWavesDT];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int parts = 1, shift = 0;                              // threads per candidate (uniform)
+    while (parts < 16 && c * (parts * 2) <= kThreadsDT) { parts *= 2; ++shift; }
+    const int per_pass = kThreadsDT >> shift;              // candidates per pass
+    const int per = ((c + parts - 1) / parts + 1) & ~1;    // others per thread, even: slices start 16-byte aligned
+    const int part = tid & (parts - 1), slot = tid >> shift;
+    const int j0 = part * per, j1 = min(j0 + per, c);
+    unsigned winbits = 0;                                  // bit p: this thread's candidate of pass p won (at most 8 passes)
+    int pass = 0;
+    for (int i0 = 0; i0 < c; i0 += per_pass, ++pass) {     // uniform trip count
+        const int i = i0 + slot;
+        const unsigned long long ki = i < c ? s_key[i] : ~0ull;
+        int beaten = 0, j = j0;
+        for (; j + 1 < j1; j += 2) {
+            const ulonglong2 q = *reinterpret_cast<const ulonglong2*>(s_key + j);
+            beaten += q.x > ki ? 1 : 0;
+            beaten += q.y > ki ? 1 : 0;
+        }
+        if (j < j1) beaten += s_key[j] > ki ? 1 : 0;
+        for (int off = 1; off < parts; off <<= 1) beaten += __shfl_xor(beaten, off);
+        if (i < c && part == 0 && beaten < M) winbits |= 1u << pass;
+    }
+    __syncthreads();                                       // the keys have been read for the last time
+    // position of a winner = winners of lower index: earlier passes, earlier wavefronts, lower lanes
+    int base = 0;
+    pass = 0;
+    for (int i0 = 0; i0 < c; i0 += per_pass, ++pass) {
+        const int i = i0 + slot;
+        const bool win = (winbits >> pass) & 1u;
+        const unsigned long long bal = __ballot(win);
+        if (lane == 0) s_wcount[wave] = __popcll(bal);
+        __syncthreads();
+        int before = base, total = 0;
+#pragma unroll
+        for (int x = 0; x < kWavesDT; ++x) {
+            const int n = s_wcount[x];
+            before += x < wave ? n : 0;
+            total += n;
+        }
+        if (i < c && part == 0)
+            reinterpret_cast<int*>(s_key)[2 * i] = win ? before + __popcll(bal & ((1ull << lane) - 1ull)) : -1;
+        base += total;
+        __syncthreads();                                   // s_wcount is rewritten by the next pass
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // draft_topk_kernel: one workgroup per (request, expanded node) row.
 //   NS > 0: every thread keeps NS vocabulary entries of the row in registers (16-byte loads
 //           when the row is aligned and V a multiple of the vector width, scalar otherwise);
@@ -142,16 +206,29 @@ __device__ __forceinline__ float wg_sum(float x, float* s_red) {
 // or, when too many do, K rounds of a workgroup-wide arg-max (every thread caches the best key
 // among its entries not yet taken; only the owner of a round's winner rescans its entries).
 // ---------------------------------------------------------------------------------------
-template <typename T, int NS>
+// SEL: the workgroup that finishes a request's last row also chooses the M most valuable of the
+// request's W*K new candidates (what draft_select_kernel does in a launch of its own): scores
+// are stored write-through, acknowledged, then a ticket per request is drawn.
+struct SelArgs {
+    int M, index_base;
+    int32_t* sel_out;
+    float* sel_score_out;
+    int32_t* count_out;
+    int32_t* counters;            // [B] tickets, zero between calls
+};
+
+template <typename T, int NS, bool SEL>
 __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
     int V, int K, const T* __restrict__ logits, int64_t stride_b, int64_t stride_w,
     const float* __restrict__ cum, int64_t cum_stride_b, const int32_t* __restrict__ parent_idx,
-    int64_t parent_stride_b, float* __restrict__ score_out, int32_t* __restrict__ token_out,
-    int32_t* __restrict__ parent_out, int64_t out_stride_b, float* __restrict__ lse_out) {
+    int64_t parent_stride_b, float* score_out, int32_t* __restrict__ token_out,
+    int32_t* __restrict__ parent_out, int64_t out_stride_b, float* __restrict__ lse_out, SelArgs sel) {
     __shared__ float s_red[kWavesDT];
     __shared__ unsigned long long s_key[2][kWavesDT];
     __shared__ int s_taken[SPECVLM_MAX_NODES];         // NS == 0: tokens already taken
-    __shared__ unsigned long long s_grp[64], s_cand[kCandCap];
+    __shared__ unsigned long long s_grp[64];
+    __shared__ __attribute__((aligned(16))) unsigned long long s_cand[kCandCap];
+    __shared__ int s_last;
     __shared__ unsigned long long s_thr;
     __shared__ int s_ncand;
 
@@ -238,7 +315,12 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
     const int64_t out0 = b * out_stride_b + static_cast<int64_t>(w) * K;
     auto emit = [&](int k, unsigned long long key) {     // k-th best of the row
         token_out[out0 + k] = static_cast<int>(0xFFFFFFFFu - static_cast<uint32_t>(key));
-        score_out[out0 + k] = c + (key_value(key) - lse);
+        const float sc = c + (key_value(key) - lse);
+        if constexpr (SEL)                               // read by another workgroup in this kernel
+            __hip_atomic_store(reinterpret_cast<uint32_t*>(score_out + out0 + k), __float_as_uint(sc),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else
+            score_out[out0 + k] = sc;
         if (parent_out) parent_out[out0 + k] = par;
     };
 
@@ -250,6 +332,7 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
     // an entry beaten by r others is the r-th best.  Keys are distinct, so the result does not
     // depend on the order in which the entries were collected.  If more than kCandCap entries
     // reach the threshold (logits sorted along the vocabulary, say) the K rounds below take over.
+    bool done = false;                                  // uniform
     {
         unsigned long long mine = 0;
         if constexpr (NS > 0) {
@@ -321,121 +404,95 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
                 for (int x = 0; x < nc; ++x) beaten += s_cand[x] > k ? 1 : 0;
                 if (beaten < K) emit(beaten, k);
             }
-            return;
+            done = true;
         }
     }
 
-    // ---- K rounds of arg-max (any input) --------------------------------------------------------
-    unsigned long long taken = 0;                       // NS > 0: bit s = entry s was taken
-    int ntaken = 0;                                     // NS == 0: length of s_taken
-    auto local_best = [&]() __attribute__((always_inline)) -> unsigned long long {
-        unsigned long long best = 0;                    // 0 = nothing left
-        if constexpr (NS > 0) {
-            best = thread_best(taken);
-        } else {
-            for (int s = 0; s < ns_mem; ++s) {
-                const int v = tid + kThreadsDT * s;
-                if (v >= V) break;
-                bool live = true;
-                for (int r = 0; r < ntaken; ++r) live = live && s_taken[r] != v;
-                if (live) {
-                    const unsigned long long k = order_key(Lane16<T>::one(row + v), v);
-                    best = k > best ? k : best;
+    if (!done) {
+        // ---- K rounds of arg-max (any input) --------------------------------------------------------
+        unsigned long long taken = 0;                       // NS > 0: bit s = entry s was taken
+        int ntaken = 0;                                     // NS == 0: length of s_taken
+        auto local_best = [&]() __attribute__((always_inline)) -> unsigned long long {
+            unsigned long long best = 0;                    // 0 = nothing left
+            if constexpr (NS > 0) {
+                best = thread_best(taken);
+            } else {
+                for (int s = 0; s < ns_mem; ++s) {
+                    const int v = tid + kThreadsDT * s;
+                    if (v >= V) break;
+                    bool live = true;
+                    for (int r = 0; r < ntaken; ++r) live = live && s_taken[r] != v;
+                    if (live) {
+                        const unsigned long long k = order_key(Lane16<T>::one(row + v), v);
+                        best = k > best ? k : best;
+                    }
                 }
             }
-        }
-        return best;
-    };
-    unsigned long long mine = local_best();
-    for (int k = 0; k < K; ++k) {
-        const unsigned long long wbest = wave_max_u64(mine);
-        if ((tid & 63) == 0) s_key[k & 1][tid >> 6] = wbest;
-        __syncthreads();                                // (the other buffer was last read two rounds ago)
-        unsigned long long win = s_key[k & 1][0];
-#pragma unroll
-        for (int x = 1; x < kWavesDT; ++x) {
-            const unsigned long long y = s_key[k & 1][x];
-            win = y > win ? y : win;
-        }
-        const int v = static_cast<int>(0xFFFFFFFFu - static_cast<uint32_t>(win));       // K <= V: never empty
-        if constexpr (NS == 0) {
-            if (tid == 0) s_taken[k] = v;
-            ++ntaken;
-            __syncthreads();
-        }
-        if (mine == win) {                              // exactly one thread: tokens are distinct
-            if constexpr (NS > 0) {
-#pragma unroll
-                for (int s = 0; s < NS; ++s)
-                    if (idx_of(s) == v) taken |= 1ull << s;
+            return best;
+        };
+        unsigned long long mine = local_best();
+        for (int k = 0; k < K; ++k) {
+            const unsigned long long wbest = wave_max_u64(mine);
+            if ((tid & 63) == 0) s_key[k & 1][tid >> 6] = wbest;
+            __syncthreads();                                // (the other buffer was last read two rounds ago)
+            unsigned long long win = s_key[k & 1][0];
+    #pragma unroll
+            for (int x = 1; x < kWavesDT; ++x) {
+                const unsigned long long y = s_key[k & 1][x];
+                win = y > win ? y : win;
             }
-            emit(k, win);
-            mine = local_best();
+            const int v = static_cast<int>(0xFFFFFFFFu - static_cast<uint32_t>(win));       // K <= V: never empty
+            if constexpr (NS == 0) {
+                if (tid == 0) s_taken[k] = v;
+                ++ntaken;
+                __syncthreads();
+            }
+            if (mine == win) {                              // exactly one thread: tokens are distinct
+                if constexpr (NS > 0) {
+    #pragma unroll
+                    for (int s = 0; s < NS; ++s)
+                        if (idx_of(s) == v) taken |= 1ull << s;
+                }
+                emit(k, win);
+                mine = local_best();
+            }
         }
     }
-}
-
-// ---------------------------------------------------------------------------------------
-// Ranking of scored candidates: candidate i beats j when score[i] > score[j], or the scores
-// are equal and i < j -- i.e. when its order_key(score, index) is the greater one.  rank(i) =
-// number of candidates that beat i; the M winners are the candidates of rank < M; a winner's
-// position is the number of winners of lower index.
-// s_key holds the c keys (16-byte aligned).  On return the low word of s_key[i] holds candidate
-// i's position among the winners, or -1 (pos_of below); the keys are gone.
-// All c*c comparisons run on one compute unit, so what counts is instructions per comparison:
-// one 64-bit compare and one add-with-carry, two keys per LDS read.  With few candidates
-// several threads share a candidate (each takes a slice of the others) so that every
-// wavefront has work.
-// ---------------------------------------------------------------------------------------
-__device__ __forceinline__ int pos_of(const unsigned long long* s_key, int i) {
-    return reinterpret_cast<const int*>(s_key)[2 * i];
-}
-
-__device__ __forceinline__ void rank_winners(unsigned long long* s_key, int c, int M) {
-    __shared__ int s_wcount[kWavesDT];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int parts = 1, shift = 0;                              // threads per candidate (uniform)
-    while (parts < 16 && c * (parts * 2) <= kThreadsDT) { parts *= 2; ++shift; }
-    const int per_pass = kThreadsDT >> shift;              // candidates per pass
-    const int per = ((c + parts - 1) / parts + 1) & ~1;    // others per thread, even: slices start 16-byte aligned
-    const int part = tid & (parts - 1), slot = tid >> shift;
-    const int j0 = part * per, j1 = min(j0 + per, c);
-    unsigned winbits = 0;                                  // bit p: this thread's candidate of pass p won (at most 8 passes)
-    int pass = 0;
-    for (int i0 = 0; i0 < c; i0 += per_pass, ++pass) {     // uniform trip count
-        const int i = i0 + slot;
-        const unsigned long long ki = i < c ? s_key[i] : ~0ull;
-        int beaten = 0, j = j0;
-        for (; j + 1 < j1; j += 2) {
-            const ulonglong2 q = *reinterpret_cast<const ulonglong2*>(s_key + j);
-            beaten += q.x > ki ? 1 : 0;
-            beaten += q.y > ki ? 1 : 0;
-        }
-        if (j < j1) beaten += s_key[j] > ki ? 1 : 0;
-        for (int off = 1; off < parts; off <<= 1) beaten += __shfl_xor(beaten, off);
-        if (i < c && part == 0 && beaten < M) winbits |= 1u << pass;
-    }
-    __syncthreads();                                       // the keys have been read for the last time
-    // position of a winner = winners of lower index: earlier passes, earlier wavefronts, lower lanes
-    int base = 0;
-    pass = 0;
-    for (int i0 = 0; i0 < c; i0 += per_pass, ++pass) {
-        const int i = i0 + slot;
-        const bool win = (winbits >> pass) & 1u;
-        const unsigned long long bal = __ballot(win);
-        if (lane == 0) s_wcount[wave] = __popcll(bal);
+    if constexpr (SEL) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's score stores have been acknowledged
         __syncthreads();
-        int before = base, total = 0;
-#pragma unroll
-        for (int x = 0; x < kWavesDT; ++x) {
-            const int n = s_wcount[x];
-            before += x < wave ? n : 0;
-            total += n;
+        if (tid == 0) {
+            int32_t* cnt = sel.counters + b;
+            const int ticket = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int last = ticket == nrows - 1;
+            if (last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = last;
         }
-        if (i < c && part == 0)
-            reinterpret_cast<int*>(s_key)[2 * i] = win ? before + __popcll(bal & ((1ull << lane) - 1ull)) : -1;
-        base += total;
-        __syncthreads();                                   // s_wcount is rewritten by the next pass
+        __syncthreads();
+        if (!s_last) return;
+        // the request's W*K new candidates (at most kCandCap, checked on the host), one per thread
+        const int nc = nrows * K;
+        float sc = 0.f;
+        if (tid < nc) {
+            sc = __uint_as_float(__hip_atomic_load(reinterpret_cast<uint32_t*>(score_out + b * out_stride_b + tid),
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            s_cand[tid] = order_key(sc, tid);
+        }
+        __syncthreads();
+        rank_winners(s_cand, nc, sel.M);
+        const int count = min(sel.M, nc);
+        if (tid < nc) {
+            const int pw = pos_of(s_cand, tid);
+            if (pw >= 0) {
+                sel.sel_out[b * sel.M + pw] = tid + sel.index_base;
+                if (sel.sel_score_out) sel.sel_score_out[b * sel.M + pw] = sc;
+            }
+        }
+        for (int pw = count + tid; pw < sel.M; pw += kThreadsDT) {
+            sel.sel_out[b * sel.M + pw] = -1;
+            if (sel.sel_score_out) sel.sel_score_out[b * sel.M + pw] = -INFINITY;
+        }
+        if (tid == 0 && sel.count_out) sel.count_out[b] = count;
     }
 }
 
@@ -524,12 +581,20 @@ int32_t launch_draft_topk(int32_t dtype, int32_t B, int32_t W, int32_t V, int32_
                           int64_t stride_b, int64_t stride_w, const float* cum, int64_t cum_stride_b,
                           const int32_t* parent_idx, int64_t parent_stride_b, float* score_out,
                           int32_t* token_out, int32_t* parent_out, int64_t out_stride_b, float* lse_out,
-                          hipStream_t stream) {
+                          int32_t M, int32_t index_base, int32_t* sel_out, float* sel_score_out,
+                          int32_t* count_out, int32_t* counters, hipStream_t stream) {
     const dim3 grid(W, B), block(kThreadsDT);
-#define SPECVLM_LAUNCH_TK(T, NS)                                                                               \
-    hipLaunchKernelGGL((draft_topk_kernel<T, NS>), grid, block, 0, stream, V, K, static_cast<const T*>(logits), \
-                       stride_b, stride_w, cum, cum_stride_b, parent_idx, parent_stride_b, score_out,          \
-                       token_out, parent_out, out_stride_b, lse_out)
+    const SelArgs sel{M, index_base, sel_out, sel_score_out, count_out, counters};
+    const bool fused = counters != nullptr;             // with the selection of the level's candidates
+#define SPECVLM_LAUNCH_TK2(T, NS, SEL)                                                                              \
+    hipLaunchKernelGGL((draft_topk_kernel<T, NS, SEL>), grid, block, 0, stream, V, K, static_cast<const T*>(logits), \
+                       stride_b, stride_w, cum, cum_stride_b, parent_idx, parent_stride_b, score_out,               \
+                       token_out, parent_out, out_stride_b, lse_out, sel)
+#define SPECVLM_LAUNCH_TK(T, NS)                                      \
+    do {                                                              \
+        if (fused) SPECVLM_LAUNCH_TK2(T, NS, true);                   \
+        else SPECVLM_LAUNCH_TK2(T, NS, false);                        \
+    } while (0)
     const int per_thread = (V + kThreadsDT - 1) / kThreadsDT;
     if (dtype == SPECVLM_BF16) {
         if (per_thread <= 32) SPECVLM_LAUNCH_TK(uint16_t, 32);
@@ -541,6 +606,7 @@ int32_t launch_draft_topk(int32_t dtype, int32_t B, int32_t W, int32_t V, int32_
         else SPECVLM_LAUNCH_TK(float, 0);
     }
 #undef SPECVLM_LAUNCH_TK
+#undef SPECVLM_LAUNCH_TK2
     return check_launch();
 }
 

@@ -122,13 +122,46 @@ def test_select_matches_oracle(sv, oracle, C, M):
     assert np.array_equal(sel2.cpu().numpy(), r2)
 
 
+@pytest.mark.parametrize("dtype,V", [("bf16", 32000), ("f32", 1000), ("bf16", 70001)])
+def test_topk_select_in_one_launch_equals_the_two_calls(sv, oracle, dtype, V):
+    """Same arithmetic in both: every output must be identical, with exact score ties between rows
+    (two rows share their logits and cumulated scores), M above and below the candidate count,
+    and twice in a row on the same counters."""
+    from gpu_util import i32, to_dev
+    rng = np.random.default_rng(V + 5)
+    B, Wd, K = 3, 7, 10
+    logits = W.normal(rng, (B, Wd, V), 2.0, dtype)
+    logits[:, 4] = logits[:, 1]
+    cum = (-rng.random((B, Wd)) * 3).astype(np.float32)
+    cum[:, 4] = cum[:, 1]
+    par = rng.integers(0, 500, size=(B, Wd)).astype(np.int32)
+    counters = torch.zeros(B, dtype=torch.int32, device="cuda")
+    lg, cm, pr = to_dev(logits), _f32(cum), i32(par)
+    score, token, parent = sv.specvlm_draft_topk(lg, K, cum=cm, parent_idx=pr)
+    for M in (10, 100):
+        sel, sel_score, count = sv.specvlm_draft_select(score, M, index_base=40)
+        f = sv.specvlm_draft_topk_select(lg, K, M, cum=cm, parent_idx=pr, index_base=40, counters=counters)
+        torch.cuda.synchronize()
+        assert torch.equal(f[0], score) and torch.equal(f[1], token) and torch.equal(f[2], parent)
+        assert torch.equal(f[3], sel) and torch.equal(f[4], sel_score) and torch.equal(f[5], count)
+        assert int(counters.sum().item()) == 0
+    # and against the oracle's selection of the oracle's own scores where the choice is clear
+    r_score, _, _ = oracle.topk_logprob(logits.reshape(B * Wd, V), K, cum.reshape(-1).astype(np.float64))
+    r_sel, r_count, r_gap = oracle.tree_select(r_score.reshape(B, Wd * K).astype(np.float32), 10)
+    sel10 = sv.specvlm_draft_topk_select(lg, K, 10, cum=cm, parent_idx=pr, counters=counters)[3].cpu().numpy()
+    for b in range(B):
+        if r_gap[b] > CLEAR or r_gap[b] == 0:
+            assert np.array_equal(sel10[b], r_sel[b])
+
+
 def _level_logits(rng, B, V, K, width, depth, dtype):
     return [W.normal(rng, (B, 1 if d == 0 else min(width, K if d == 1 else width * K), V), 2.0, dtype)
             for d in range(depth)]
 
 
-def _grow_on_gpu(sv, level_logits, root_token, K, width, N_max):
-    """The caller's loop: one select + topk per level, writing into the request's candidate arrays."""
+def _grow_on_gpu(sv, level_logits, root_token, K, width, N_max, fused=False):
+    """The caller's loop: one select + topk per level, writing into the request's candidate arrays.
+    fused: the selection for the next level is made by the level's own launch."""
     from gpu_util import i32, to_dev
     B = level_logits[0].shape[0]
     C = sum(lg.shape[1] * K for lg in level_logits)
@@ -136,18 +169,26 @@ def _grow_on_gpu(sv, level_logits, root_token, K, width, N_max):
     token = torch.zeros((B, C), dtype=torch.int32, device="cuda")
     parent = torch.full((B, C), -1, dtype=torch.int32, device="cuda")
     base, count, sels = 0, 0, []
+    counters = torch.zeros(B, dtype=torch.int32, device="cuda")
+    sel = sel_score = None
     for d, lg in enumerate(level_logits):
         rows = lg.shape[1]
         new_base = base + count
         out = dict(score_out=score[:, new_base:new_base + rows * K], token_out=token[:, new_base:new_base + rows * K],
                    parent_out=parent[:, new_base:new_base + rows * K])
-        if d == 0:
-            sv.specvlm_draft_topk(to_dev(lg), K, **out)
-        else:
+        if d > 0 and not fused:
             sel, sel_score, _ = sv.specvlm_draft_select(score[:, base:base + count], rows, index_base=base)
+        if d > 0:
             sels.append(sel.cpu().numpy())
+        if fused and d + 1 < len(level_logits):
+            nxt = level_logits[d + 1].shape[1]
+            res = sv.specvlm_draft_topk_select(to_dev(lg), K, nxt, cum=sel_score, parent_idx=sel, index_base=new_base,
+                                               counters=counters, **out)
+            sel, sel_score = res[3], res[4]
+        else:
             sv.specvlm_draft_topk(to_dev(lg), K, cum=sel_score, parent_idx=sel, **out)
         base, count = new_base, rows * K
+    assert int(counters.sum().item()) == 0
     err = torch.zeros(1, dtype=torch.int32, device="cuda")
     par, tok, node_cand, num_nodes = sv.specvlm_draft_finalize(score, parent, token, i32(root_token), N_max, err_flag=err)
     assert int(err.item()) == 0
@@ -163,12 +204,13 @@ def _grow_on_gpu(sv, level_logits, root_token, K, width, N_max):
     ("small-f32", 3, 1000, 4, 6, 5, 24, "f32"),
     ("wide", 2, 5000, 8, 20, 4, 64, "bf16"),
 ])
-def test_whole_growth_matches_oracle(sv, oracle, name, B, V, K, width, depth, N_max, dtype):
+@pytest.mark.parametrize("fused", [False, True])
+def test_whole_growth_matches_oracle(sv, oracle, name, B, V, K, width, depth, N_max, dtype, fused):
     rng = np.random.default_rng(W.config_seed(W.CONFIGS["C3"], 0, 7) + B * 131 + V)
     lv = _level_logits(rng, B, V, K, width, depth, dtype)
     root = rng.integers(0, V, size=B).astype(np.int32)
     ref = oracle.grow_tree(lv, root, K=K, width=width, N_max=N_max)
-    got = _grow_on_gpu(sv, lv, root, K, width, N_max)
+    got = _grow_on_gpu(sv, lv, root, K, width, N_max, fused=fused)
     gaps = np.stack(ref["level_gap"] + [ref["final_gap"]])             # [levels+1, B]
     # an exact tie (margin 0: equal logits under one parent give equal scores on both sides) is
     # decided by the index rule; only a small non-zero margin is ambiguous
