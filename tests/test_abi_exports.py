@@ -53,6 +53,12 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.specvlm_draft_topk(0, 1, 1, 10, 11, *([null, 0, 10] + [null, 0] * 2 + [null] * 3 + [11, null, null])) == 1
     assert lib.specvlm_draft_topk(0, 1, 1, 100, 65, *([null, 0, 100] + [null, 0] * 2 + [null] * 3 + [65, null, null])) == 1
     assert lib.specvlm_draft_select(1, 8193, 4, null, 8193, null, 0, null, null, null, null) == 1
+    # fused level: more than 1024 new candidates, or no ticket counters (pointers are never touched: the checks come first)
+    fake = ctypes.c_void_p(4096)
+    level = [fake, 0, 32000, null, 0, null, 0, fake, fake, null]
+    assert lib.specvlm_draft_topk_select(0, 1, 103, 32000, 10, *level, 1030, null, 10, 0, fake, null, null, fake, null) == 1
+    assert lib.specvlm_draft_topk_select(0, 1, 10, 32000, 10, *level, 100, null, 10, 0, fake, null, null, null, null) == 1
+    assert lib.specvlm_draft_topk_select(0, 1, 10, 32000, 10, *level, 100, null, 0, 0, fake, null, null, fake, null) == 1
     assert lib.specvlm_draft_finalize(1, 100, 65, null, null, null, 100, *([null] * 8)) == 1
 
 
