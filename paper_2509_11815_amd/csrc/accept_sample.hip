@@ -113,6 +113,20 @@ __global__ __launch_bounds__(kThreadsAS) void tree_accept_sample_kernel(
     float lv[CH > 0 ? CH : 1];                          // this thread's logits of the current row
     for (;;) {
         const T* row = base + cur * stride_n;
+        // Wavefront 0, lane c: child c's logit and uniform number, requested now so that they
+        // arrive while the row is reduced (a dependent load after the reductions would add a
+        // memory round trip to every level of the walk).
+        bool is_child = false;
+        float child_logit = 0.f, child_u = 1.f;
+        int child_tok = -1;
+        if (tid < SPECVLM_MAX_NODES) {
+            is_child = tid > cur && tid < n && s_par[tid] == cur;
+            if (is_child) {
+                child_tok = s_tok[tid];
+                if (child_tok >= 0 && child_tok < V) child_logit = logit_at<T>(row, child_tok);
+                child_u = u_accept[b * N_max + tid];
+            }
+        }
         // target distribution at cur, unnormalised: e(v) = exp((l_v - max) / T)
         float part = -INFINITY;
         if constexpr (CH > 0) {
@@ -161,15 +175,10 @@ __global__ __launch_bounds__(kThreadsAS) void tree_accept_sample_kernel(
         // the candidates of cur, prepared in parallel: lane c holds child c's unnormalised
         // probability and uniform number, so that the sequential decisions below wait for no load
         if (tid < SPECVLM_MAX_NODES) {                  // wavefront 0
-            float ex = -1.f, u = 1.f;                   // ex < 0 marks "token out of range"
-            const bool is_child = tid > cur && tid < n && s_par[tid] == cur;
-            if (is_child) {
-                const int x = s_tok[tid];
-                if (x >= 0 && x < V) ex = prob_of(logit_at<T>(row, x));
-                u = u_accept[b * N_max + tid];
-            }
+            float ex = -1.f;                            // ex < 0 marks "token out of range"
+            if (is_child && child_tok >= 0 && child_tok < V) ex = prob_of(child_logit);
             s_cex[tid] = ex;
-            s_cu[tid] = u;
+            s_cu[tid] = child_u;
             const unsigned long long kids = __ballot(is_child);
             if (tid == 0) s_kids = kids;
         }
