@@ -279,3 +279,34 @@ def test_paged_pool_larger_than_4_gib(sv, oracle):
     ref, _ = oracle.tree_attn(case["q"], case["k"], case["v"], case["prefix_len"], case["parent"],
                               block_table=case["block_table"])
     assert_attn_close(to_host_f64(out), ref, "bf16", "large paged pool")
+
+
+def test_two_streams_with_their_own_workspaces(sv, oracle):
+    """Calls on two HIP streams overlap freely as long as each stream has its own workspace:
+    20 calls per stream, issued alternately, every output equal to the same call made alone."""
+    from gpu_util import random_case, i32, to_dev, to_host_f64, assert_attn_close
+    cases = [random_case(81, "bf16", B=1, Hq=8, Hkv=8, D=128, N_max=60, P_list=[2000]),
+             random_case(82, "bf16", B=2, Hq=4, Hkv=2, D=128, N_max=33, P_list=[700, 1300])]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    dev, alone, ws, outs = [], [], [], []
+    for c in cases:
+        t = dict(q=to_dev(c["q"]), k=to_dev(c["k"]), v=to_dev(c["v"]), P=i32(c["prefix_len"]), par=i32(c["parent"]))
+        desc = sv.binding.make_attn_desc(t["q"], t["k"], t["q"], num_splits=8)
+        t["desc"] = desc
+        dev.append(t)
+        ws.append(torch.zeros(sv.specvlm_tree_verify_attn_workspace_bytes(desc), dtype=torch.uint8, device="cuda"))
+        alone.append(sv.specvlm_tree_verify_attn(t["q"], t["k"], t["v"], t["P"], t["par"], desc=desc).clone())
+        outs.append([torch.zeros_like(t["q"]) for _ in range(20)])
+    torch.cuda.synchronize()
+    for it in range(20):
+        for s in range(2):
+            t = dev[s]
+            with torch.cuda.stream(streams[s]):
+                sv.specvlm_tree_verify_attn(t["q"], t["k"], t["v"], t["P"], t["par"], out=outs[s][it],
+                                            workspace=ws[s], desc=t["desc"], stream=streams[s])
+    torch.cuda.synchronize()
+    for s in range(2):
+        for it in range(20):
+            assert torch.equal(outs[s][it], alone[s]), f"stream {s} call {it}"
+        ref, _ = oracle.tree_attn(cases[s]["q"], cases[s]["k"], cases[s]["v"], cases[s]["prefix_len"], cases[s]["parent"])
+        assert_attn_close(to_host_f64(alone[s]), ref, "bf16", f"stream {s}")
