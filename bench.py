@@ -49,6 +49,8 @@ def parse_args():
     ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--skip-ceilings", action="store_true", help="skip the library copy / read-only bandwidth legs")
     ap.add_argument("--attn-only", action="store_true", help="profile helper: run only the attention launches")
+    ap.add_argument("--pool-only", action="store_true",
+                    help="profile helper: run only the visual-token pooling launches (8 requests of 2880 x 4096, ratio 20)")
     ap.add_argument("--head-only", action="store_true", help="profile helper: run only the fused output-head launches")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profile helper: run plain device copies of a known size (scale for the HBM byte counters)")
@@ -174,6 +176,23 @@ def main():
 
         ms = timed(make_runner(head_calls), args.steps, args.warmup) / len(heads)
         print(json.dumps({"head_argmax_ms_per_call": ms}))
+        return
+    if args.pool_only:
+        # eight requests' visual features (2880 tokens x 4096, the 7B-shaped projector output) pooled 20x;
+        # eight input copies are cycled so that none is served from the 256 MB cache
+        Bp, Tp, Ep, rp = 8, 2880, 4096, 20
+        xs = [torch.randn((Bp, Tp, Ep), device=dev).to(torch.bfloat16) for _ in range(8)]
+        yp = torch.zeros((Bp, (Tp + rp - 1) // rp, Ep), dtype=torch.bfloat16, device=dev)
+        ntok = torch.empty(Bp, dtype=torch.int32, device=dev)
+
+        def pool_calls():
+            for xp in xs:
+                sv.specvlm_visual_pool(xp, rp, out=yp, out_tokens=ntok)
+
+        ms = timed(make_runner(pool_calls), args.steps, args.warmup) / len(xs)
+        nbytes = xs[0].numel() * 2 + yp.numel() * 2
+        print(json.dumps({"visual_pool_ms_per_call": ms, "bytes_per_call": nbytes,
+                          "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_of_8TBps": round(nbytes / (ms * 1e-3) / 8e12, 4)}))
         return
     if args.attn_only:
         run_attn = make_runner(attn_layers)
