@@ -28,8 +28,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/),
 # keyed by workload; None until measured.
 MEASURED_TRAFFIC = {
-    # profiles/attn_mfma_kernel_C3.txt: 29068.7 FETCH_SIZE units x 2.000 KiB + 4868.0 WRITE_SIZE units x 1.000 KiB
-    "C3": {"read_bytes": 59532698, "write_bytes": 4984832, "bytes": 64517530},
+    # profiles/attn_mfma_kernel_C3.txt: 29073.7 FETCH_SIZE units x 2.000 KiB + 4740.0 WRITE_SIZE units x 1.000 KiB
+    "C3": {"read_bytes": 59542937, "write_bytes": 4853760, "bytes": 64396697},
 }
 # the same for the fused output head (profiles/head_argmax_kernel_C3.txt); None until measured
 MEASURED_TRAFFIC_HEAD = {
