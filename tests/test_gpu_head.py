@@ -52,6 +52,8 @@ def _check(sv, oracle, h, w, nn=None):
     (2, 64, 384, 3000),        # exactly two node blocks
     (6, 64, 128, 300),         # six node blocks share one pass over W
     (9, 60, 256, 2000),        # 540 rows: a group of eight node blocks and a second group with one
+    (1, 60, 128, 40000),       # 313 vocabulary tiles: the last workgroup's reduction takes two batches of loads
+    (2, 33, 128, 70001),       # 547 tiles, ragged last tile, two node blocks
 ])
 def test_matches_oracle(sv, oracle, B, N, E, V):
     rng = np.random.default_rng(B * 1000 + V)
