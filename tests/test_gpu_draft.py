@@ -122,7 +122,7 @@ def test_select_matches_oracle(sv, oracle, C, M):
     assert np.array_equal(sel2.cpu().numpy(), r2)
 
 
-@pytest.mark.parametrize("dtype,V", [("bf16", 32000), ("f32", 1000), ("bf16", 70001)])
+@pytest.mark.parametrize("dtype,V", [("bf16", 32000), ("f32", 1000), ("bf16", 40000), ("bf16", 70001)])
 def test_topk_select_in_one_launch_equals_the_two_calls(sv, oracle, dtype, V):
     """Same arithmetic in both: every output must be identical, with exact score ties between rows
     (two rows share their logits and cumulated scores), M above and below the candidate count,
@@ -132,6 +132,7 @@ def test_topk_select_in_one_launch_equals_the_two_calls(sv, oracle, dtype, V):
     B, Wd, K = 3, 7, 10
     logits = W.normal(rng, (B, Wd, V), 2.0, dtype)
     logits[:, 4] = logits[:, 1]
+    logits[:, 6] = np.sort(logits[:, 6], axis=-1)       # best tokens are neighbours: the K-rounds path
     cum = (-rng.random((B, Wd)) * 3).astype(np.float32)
     cum[:, 4] = cum[:, 1]
     par = rng.integers(0, 500, size=(B, Wd)).astype(np.int32)
