@@ -224,20 +224,10 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     // between would make the compiler's own wait drain every tile still in flight.  The two
     // request scalars come through the scalar cache (constant address space, uniform index).
     typedef const __attribute__((address_space(4))) int32_t* const_i32;
-    int err = 0;
-    int n = p.num_nodes ? ((const_i32)p.num_nodes)[b] : p.N_max;
-    const int P = ((const_i32)p.prefix_len)[b];
-    if (n < 1 || n > p.N_max) err |= SPECVLM_ERR_BAD_NUM_NODES;
-    n = min(max(n, 1), p.N_max);
-    if (P < 0 || P + n > p.g.capacity) err |= SPECVLM_ERR_BAD_LENGTH;
-    const int S = P + n;
+    const int n_raw = p.num_nodes ? ((const_i32)p.num_nodes)[b] : p.N_max;
+    const int P_raw = ((const_i32)p.prefix_len)[b];
     const int nstream = kStreams * p.num_splits;
     const int stream = split * kStreams + st;
-    const int ntile = (S + kTile - 1) / kTile;                       // 32-key tiles of this request
-    // tiles stream, stream + nstream, ... ; none when the lengths are bad (nothing may be fetched then)
-    const int my_tiles = (!err && stream < ntile) ? (ntile - stream + nstream - 1) / nstream : 0;
-    // the workgroup's first stream has the most tiles: the (uniform) trip count of the main loop
-    const int wg_tiles = (!err && split * kStreams < ntile) ? (ntile - split * kStreams + nstream - 1) / nstream : 0;
 
     unsigned char* ring = s_ring + st * kRingBytes;
     typedef __attribute__((address_space(3))) unsigned char lds_byte;
@@ -266,23 +256,13 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
 #pragma unroll
     for (int ii = 0; ii < KPW; ++ii)
         voff_v[ii] = lrow * row_bytes + vgran((qw * KPW + ii) * RPI + lrow) * 16;
-    // Paged cache: physical ids of the two 16-key blocks of a tile, through the scalar cache.
-    // They are looked up one tile ahead of the loads that need them, so the look-up latency
-    // never sits between a free ring slot and its refill.
-    auto fetch_blocks = [&](int j, int (&phys)[2]) {
-        if (!p.g.block_table) return;
-        const int blk0 = (stream + j * nstream) * (kTile >> 4), last_blk = (S - 1) >> 4;
-#pragma unroll
-        for (int x = 0; x < 2; ++x)
-            phys[x] = ((const_i32)p.g.block_table)[static_cast<int64_t>(b) * p.g.max_blocks + min(blk0 + x, last_blk)];
-    };
     const int64_t head_off = hk * p.g.stride_h + (p.g.block_table ? 0 : b * p.g.stride_b);   // elements
     // A wavefront requests its 32/WQ rows of the stream's tile, K and V: KPW loads each, into the
     // two areas of the slot that only this wavefront ever fills.
     const uint32_t area = qw * KPW * 1024;                // this wavefront's area inside a K (or V) tile
-    auto issue_part = [&](int j, const int (&phys)[2]) {
+    auto issue_rows = [&](int j, int lim, const int (&phys)[2]) __attribute__((always_inline)) {   // lim: first row that must not be fetched
         const uint32_t dst = ring_lds + (j % kSlots) * kSlotBytes;
-        const int lo = (stream + j * nstream) * kTile, lim = S;          // first key, and the request's end
+        const int lo = (stream + j * nstream) * kTile;                   // first key
 #pragma unroll
         for (int ii = 0; ii < KPW; ++ii) {
             const int i = qw * KPW + ii;
@@ -306,21 +286,55 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
             dma16s(p.v + base, vv, dst + kTileBytes + i * 1024);
         }
     };
+    // The stream's first tile is requested before the request's lengths are known (they arrive
+    // through the scalar cache half a microsecond into the kernel): with a contiguous cache its
+    // address needs nothing else, and a tile inside the cache's capacity is memory that may be
+    // read.  If the lengths then show that the tile is not entirely real, it is requested again
+    // the ordinary way (rows past the last key re-read that key's row).
+    // (Sending the query rows out early as well made the call slower: 17.2 against 17.0 us.)
+    int phys[2] = {0, 0};
+    const bool early = !p.g.block_table && (stream + 1) * kTile <= p.g.capacity;     // uniform
+    if (early) issue_rows(0, p.g.capacity, phys);
+    int err = 0;
+    int n = n_raw;
+    const int P = P_raw;
+    if (n < 1 || n > p.N_max) err |= SPECVLM_ERR_BAD_NUM_NODES;
+    n = min(max(n, 1), p.N_max);
+    if (P < 0 || P + n > p.g.capacity) err |= SPECVLM_ERR_BAD_LENGTH;
+    const int S = P + n;
+    const int ntile = (S + kTile - 1) / kTile;                       // 32-key tiles of this request
+    // tiles stream, stream + nstream, ... ; none when the lengths are bad (nothing more may be fetched then)
+    const int my_tiles = (!err && stream < ntile) ? (ntile - stream + nstream - 1) / nstream : 0;
+    // the workgroup's first stream has the most tiles: the (uniform) trip count of the main loop
+    const int wg_tiles = (!err && split * kStreams < ntile) ? (ntile - split * kStreams + nstream - 1) / nstream : 0;
+    // the early request is the stream's first tile if that tile exists and every row of it is real
+    const bool first_done = early && my_tiles > 0 && (stream + 1) * kTile <= S;
+    if (early && !first_done) wait_vmcnt<0>();          // rare: let it land (unused rows of the slot), then go on as without it
+    auto issue_part = [&](int j, const int (&ph)[2]) __attribute__((always_inline)) { issue_rows(j, S, ph); };
+    // Paged cache: physical ids of the two 16-key blocks of a tile, through the scalar cache.
+    // They are looked up one tile ahead of the loads that need them, so the look-up latency
+    // never sits between a free ring slot and its refill.
+    auto fetch_blocks = [&](int j, int (&phys)[2]) {
+        if (!p.g.block_table) return;
+        const int blk0 = (stream + j * nstream) * (kTile >> 4), last_blk = (S - 1) >> 4;
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+            phys[x] = ((const_i32)p.g.block_table)[static_cast<int64_t>(b) * p.g.max_blocks + min(blk0 + x, last_blk)];
+    };
     typedef __attribute__((address_space(3))) int lds_int;
-    // Oldest in the queue: the parent array (wavefront 0; lanes past N_max re-read its last entry),
+    // Next in the queue: the parent array (wavefront 0; lanes past N_max re-read its last entry),
     // which is waited for on its own, so that the tree is checked and the ancestor masks are built
-    // while everything else is still in flight.  Then this wavefront's share of the first tile and
-    // its QW query rows (B operand of S^T = K Q^T), XOR-swizzled like the K tiles and staged in the
-    // ring's last slot -- first half of the rows in this wavefront's K area, second half in its V
-    // area, the two areas only this wavefront refills later, so no other wavefront can overwrite
-    // them before they are read (query rows past the node count re-read the last real row; their
-    // columns of S^T are never stored).  Those are what the first step needs; the tiles further
-    // ahead come after.
+    // while the tiles are still in flight.  Then, unless it went out early, this wavefront's share
+    // of the first tile, and its query rows -- staged in the ring's last slot, first half of the
+    // rows in this wavefront's K area, second half in its V area, the two areas only this
+    // wavefront refills later, so no other wavefront can overwrite them before they are read.
+    // Those are what the first step needs; the tiles further ahead come after.
     if (wave == 0)
         dma4(p.parent + static_cast<int64_t>(b) * p.N_max + min(lane, p.N_max - 1),
              (uint32_t)(uintptr_t)(lds_int*)s_par);
-    int phys[2] = {0, 0};
-    if (my_tiles > 0) { fetch_blocks(0, phys); issue_part(0, phys); }
+    if (my_tiles > 0 && !first_done) { fetch_blocks(0, phys); issue_part(0, phys); }
+    // this wavefront's QW query rows (B operand of S^T = K Q^T), XOR-swizzled like the K tiles; rows
+    // past the node count re-read the last real row (their columns of S^T are never stored)
     constexpr uint32_t kStage = (kSlots - 1) * kSlotBytes;
 #pragma unroll
     for (int i = 0; i < 2 * KPW; ++i) {
@@ -345,7 +359,10 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     const float c2 = p.scale * kLog2e;
     // ---- the tree: checked once; ancestor-or-self masks of this lane's query rows -----------------
     if (wave == 0) {
-        if (min(PD, my_tiles) == PD) wait_vmcnt<(PD + 1) * NI>(); else wait_tiles(min(PD, my_tiles) + 1);
+        // requested after the parent array: the query rows and the tiles in flight, except a
+        // first tile that went out early
+        const int after_parent = min(PD, my_tiles) + 1 - (first_done ? 1 : 0);
+        if (after_parent == PD + 1) wait_vmcnt<(PD + 1) * NI>(); else wait_tiles(after_parent);
     }
     __syncthreads();
     {

@@ -63,6 +63,8 @@ def random_case(seed, dtype, B, Hq, Hkv, D, N_max, P_list, *, num_nodes=None, pa
     parent = np.stack([W.chain_tree(N_max) if tree == "chain" else W.random_tree(rng, N_max, depth)
                        for _ in range(B)])
     poison = W.NAN_BITS_BF16 if dtype == "bf16" else np.float32(np.nan)
+    for b in range(B):                                   # query rows past the node count are never to matter
+        q[b, nn[b]:] = poison
     if not paged:
         cap = W.round_up(int(S.max()) + cap_extra, 8)
         k = W.normal(rng, (B, Hkv, cap, D), 1.0, dtype)
