@@ -310,3 +310,15 @@ def test_two_streams_with_their_own_workspaces(sv, oracle):
             assert torch.equal(outs[s][it], alone[s]), f"stream {s} call {it}"
         ref, _ = oracle.tree_attn(cases[s]["q"], cases[s]["k"], cases[s]["v"], cases[s]["prefix_len"], cases[s]["parent"])
         assert_attn_close(to_host_f64(alone[s]), ref, "bf16", f"stream {s}")
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_capacity_far_above_the_lengths(sv, oracle, D):
+    """A contiguous cache much longer than the requests (poisoned beyond their ends): first tiles
+    that lie inside the capacity but partly or wholly past a request's last key."""
+    from gpu_util import random_case
+    for seed, P_list, nodes in ((91, [100, 3, 1000], [60, 5, 33]), (92, [0, 517, 31], [1, 64, 40])):
+        case = random_case(seed, "bf16", B=3, Hq=4, Hkv=2, D=D, N_max=64, P_list=P_list, num_nodes=nodes,
+                           cap_extra=3000)
+        for splits in (0, 1, 3, 8, 16):
+            check(case, *run_both(sv, oracle, case, num_splits=splits), f"seed {seed} D={D} splits={splits}")
