@@ -266,7 +266,7 @@ def main():
             sv.specvlm_head_argmax(hid, w, out=h_out, workspace=h_ws)
 
     ms_head = timed(make_runner(head_calls), max(args.steps // 4, 5), 3) / len(heads)
-    head_bytes = cfg.V * E_h * 2 * ((B * N + 63) // 64)
+    head_bytes = cfg.V * E_h * 2          # the head matrix once, however many blocks of 64 node rows share the pass
     assert int(err.item()) == 0, "device error flag set"
 
     kv_bytes_layer = W.kv_bytes_per_layer(cfg)
