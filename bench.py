@@ -166,7 +166,7 @@ def main():
     if args.head_only:
         E_h = 128 * H
         hid = torch.randn((B, N, E_h), device=dev).to(torch.bfloat16)
-        heads = [torch.randn((cfg.V, E_h), device=dev).mul_(2.0 / E_h ** 0.5).to(torch.bfloat16) for _ in range(8)]
+        heads = [torch.empty((cfg.V, E_h), dtype=torch.bfloat16, device=dev).normal_(0.0, 2.0 / E_h ** 0.5) for _ in range(8)]
         h_ws = torch.zeros(sv.specvlm_head_argmax_workspace_bytes(B, N, cfg.V), dtype=torch.uint8, device=dev)
         h_out = torch.empty((B, N), dtype=torch.int32, device=dev)
 
@@ -269,7 +269,8 @@ def main():
     # Eight copies of the head matrix are cycled so that none is served from the 256 MB cache.
     E_h = 128 * H
     hid = torch.randn((B, N, E_h), device=dev, generator=gen).to(torch.bfloat16)
-    heads = [torch.randn((cfg.V, E_h), device=dev, generator=gen).mul_(2.0 / E_h ** 0.5).to(torch.bfloat16)
+    # (drawn in bf16 directly: fp32 temporaries twice the size would fragment the allocator's memory)
+    heads = [torch.empty((cfg.V, E_h), dtype=torch.bfloat16, device=dev).normal_(0.0, 2.0 / E_h ** 0.5, generator=gen)
              for _ in range(8)]
     h_ws = torch.zeros(sv.specvlm_head_argmax_workspace_bytes(B, N, cfg.V), dtype=torch.uint8, device=dev)
     h_out = torch.empty((B, N), dtype=torch.int32, device=dev)
