@@ -21,7 +21,8 @@
 //             streaming the chip is saturated at that depth, more in flight measured
 //             slower.  Completion is tracked by hand with
 //             s_waitcnt vmcnt, and one workgroup barrier per tile publishes the landed
-//             shares and frees the consumed slot
+//             shares and frees the consumed slot.  With a contiguous cache a stream's first
+//             tile is requested before the request's lengths have arrived
 //   QK^T      S^T[32 keys x 64 q] = K . Q^T with v_mfma_f32_16x16x32_bf16; the lanes fetch
 //             K granules in XOR-swizzled order so that the operand reads (16 different rows
 //             per 16 lanes) are free of LDS bank conflicts; a wavefront's Q fragments stay in
