@@ -139,10 +139,10 @@ __device__ __forceinline__ float wg_sum(float x, float* s_red) {
 // position is the number of winners of lower index.
 // s_key holds the c keys (16-byte aligned).  On return the low word of s_key[i] holds candidate
 // i's position among the winners, or -1 (pos_of below); the keys are gone.
-// All c*c comparisons run on one compute unit, so what counts is instructions per comparison:
-// one 64-bit compare and one add-with-carry, two keys per LDS read.  With few candidates
-// several threads share a candidate (each takes a slice of the others) so that every
-// wavefront has work.
+// All c*c comparisons run on one compute unit, so what counts is instructions per comparison
+// (two, see below) and that every wavefront has work: with few candidates several groups of
+// wavefronts share the candidates, each taking a slice of the others.  s_key needs room for an
+// even number of keys.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ int pos_of(const unsigned long long* s_key, int i) {
     return reinterpret_cast<const int*>(s_key)[2 * i];
@@ -150,26 +150,60 @@ __device__ __forceinline__ int pos_of(const unsigned long long* s_key, int i) {
 
 __device__ __forceinline__ void rank_winners(unsigned long long* s_key, int c, int M) {
     __shared__ int s_wcount[kWavesDT];
+    __shared__ int s_cnt[kThreadsDT];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int parts = 1, shift = 0;                              // threads per candidate (uniform)
-    while (parts < 16 && c * (parts * 2) <= kThreadsDT) { parts *= 2; ++shift; }
-    const int per_pass = kThreadsDT >> shift;              // candidates per pass
-    const int per = ((c + parts - 1) / parts + 1) & ~1;    // others per thread, even: slices start 16-byte aligned
-    const int part = tid & (parts - 1), slot = tid >> shift;
-    const int j0 = part * per, j1 = min(j0 + per, c);
+    // `parts` groups of wavefronts share the candidates of a pass: group `part` counts, for every
+    // candidate of the pass, the keys of its slice [j0, j1) of the others that beat it.
+    int parts = 1, shift = 0;                              // uniform; a group is at least one wavefront
+    while (parts < kWavesDT && c * (parts * 2) <= kThreadsDT) { parts *= 2; ++shift; }
+    const int per_pass = kThreadsDT >> shift;              // candidates per pass (>= 64)
+    const int part = tid / per_pass, slot = tid & (per_pass - 1);
+    const int c_even = (c + 1) & ~1;                       // keys are read in pairs: an odd count is padded with a key nothing loses to
+    if (tid == 0 && (c & 1)) s_key[c] = 0ull;
+    __syncthreads();
+    const int per = ((c_even / 2 + parts - 1) / parts) * 2;
+    const int j0 = min(part * per, c_even), j1 = min(j0 + per, c_even);
     unsigned winbits = 0;                                  // bit p: this thread's candidate of pass p won (at most 8 passes)
     int pass = 0;
     for (int i0 = 0; i0 < c; i0 += per_pass, ++pass) {     // uniform trip count
         const int i = i0 + slot;
         const unsigned long long ki = i < c ? s_key[i] : ~0ull;
-        int beaten = 0, j = j0;
-        for (; j + 1 < j1; j += 2) {
+        const uint32_t hi = static_cast<uint32_t>(ki >> 32);
+        // The candidates of this wavefront are iw0 .. iw0 + 63.  A key j below all of them beats
+        // candidate i when its upper word is >= i's (equal scores: the lower index wins), a key
+        // above all of them when it is > : one 32-bit compare and an add-with-carry per key (a
+        // 64-bit compare runs at a quarter of that rate).  Only the keys among the wavefront's own
+        // candidates need the whole key.  (No score is NaN, so an upper word is never 0.)
+        const int iw0 = i0 + ((wave * 64) & (per_pass - 1));
+        const int a_end = max(j0, min(j1, iw0 & ~1));             // pairs entirely below iw0
+        const int b_end = max(a_end, min(j1, (iw0 + 65) & ~1));   // pairs that may hold one of the wavefront's candidates
+        int beaten = 0;
+        const uint32_t thr_below = hi - 1u;
+#pragma unroll 4
+        for (int j = j0; j < a_end; j += 2) {
+            const ulonglong2 q = *reinterpret_cast<const ulonglong2*>(s_key + j);
+            beaten += static_cast<uint32_t>(q.x >> 32) > thr_below ? 1 : 0;
+            beaten += static_cast<uint32_t>(q.y >> 32) > thr_below ? 1 : 0;
+        }
+        for (int j = a_end; j < b_end; j += 2) {
             const ulonglong2 q = *reinterpret_cast<const ulonglong2*>(s_key + j);
             beaten += q.x > ki ? 1 : 0;
             beaten += q.y > ki ? 1 : 0;
         }
-        if (j < j1) beaten += s_key[j] > ki ? 1 : 0;
-        for (int off = 1; off < parts; off <<= 1) beaten += __shfl_xor(beaten, off);
+#pragma unroll 4
+        for (int j = b_end; j < j1; j += 2) {
+            const ulonglong2 q = *reinterpret_cast<const ulonglong2*>(s_key + j);
+            beaten += static_cast<uint32_t>(q.x >> 32) > hi ? 1 : 0;
+            beaten += static_cast<uint32_t>(q.y >> 32) > hi ? 1 : 0;
+        }
+        if (parts > 1) {                                   // uniform: add the groups' counts up
+            if (part == 0) s_cnt[slot] = 0;
+            __syncthreads();
+            atomicAdd(&s_cnt[slot], beaten);
+            __syncthreads();
+            beaten = s_cnt[slot];
+            __syncthreads();                               // s_cnt is cleared again by the next pass
+        }
         if (i < c && part == 0 && beaten < M) winbits |= 1u << pass;
     }
     __syncthreads();                                       // the keys have been read for the last time
@@ -613,7 +647,7 @@ int32_t launch_draft_topk(int32_t dtype, int32_t B, int32_t W, int32_t V, int32_
 int32_t launch_draft_select(int32_t B, int32_t C, int32_t M, const float* score, int64_t score_stride_b,
                             const int32_t* num_cand, int32_t index_base, int32_t* sel_out,
                             float* sel_score_out, int32_t* count_out, hipStream_t stream) {
-    const size_t lds = static_cast<size_t>(C) * 8;
+    const size_t lds = static_cast<size_t>((C + 1) & ~1) * 8;         // keys are ranked in pairs
     hipLaunchKernelGGL(draft_select_kernel, dim3(B), dim3(kThreadsDT), lds, stream, C, M, score, score_stride_b,
                        num_cand, index_base, sel_out, sel_score_out, count_out);
     return check_launch();
@@ -624,7 +658,7 @@ int32_t launch_draft_finalize(int32_t B, int32_t C, int32_t N_max, const float* 
                               const int32_t* num_cand, const int32_t* root_token, int32_t* parent_out,
                               int32_t* draft_tok_out, int32_t* node_cand_out, int32_t* num_nodes_out,
                               int32_t* err_flag, hipStream_t stream) {
-    const size_t lds = static_cast<size_t>(C) * 8;
+    const size_t lds = static_cast<size_t>((C + 1) & ~1) * 8;         // keys are ranked in pairs
     hipLaunchKernelGGL(draft_finalize_kernel, dim3(B), dim3(kThreadsDT), lds, stream, C, N_max, cand_score,
                        cand_parent, cand_token, cand_stride_b, num_cand, root_token, parent_out, draft_tok_out,
                        node_cand_out, num_nodes_out, err_flag);
