@@ -47,8 +47,9 @@ def parse_args():
     ap.add_argument("--splits", type=int, default=0, help="key-range splits per (request, head); 0 = library default")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU oracle baseline leg")
-    ap.add_argument("--skip-evidence", action="store_true",
-                    help="skip the layers-folded-into-one-call leg (keeps a kernel trace's per-call averages clean)")
+    ap.add_argument("--evidence", action="store_true",
+                    help="also time all layers folded into one batched attention call (evidence only; off by default so "
+                         "that a kernel trace of the default run holds per-layer calls only)")
     ap.add_argument("--skip-ceilings", action="store_true", help="skip the library copy / read-only bandwidth legs")
     ap.add_argument("--attn-only", action="store_true", help="profile helper: run only the attention launches")
     ap.add_argument("--pool-only", action="store_true",
@@ -211,7 +212,7 @@ def main():
     # before -- but it shows what the kernel streams once the per-call fixed costs (launch, first-tile
     # latency, the merge of the splits) are paid once instead of L times.
     ms_folded = None
-    if not cfg.paged and not args.skip_evidence:
+    if not cfg.paged and args.evidence:
         qf, kf, vf, of = (t.view(L * B, *t.shape[2:]) for t in (q, k, v, out))
         pf, parf = prefix_len.repeat(L), parent.repeat(L, 1)
         dfold = sv.binding.make_attn_desc(qf, kf, of)
