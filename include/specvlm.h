@@ -69,6 +69,8 @@ typedef enum specvlm_dtype {
  *              (logical slot s of request b lives in block block_table[b][s/16], row s%16).
  *   K and V share one geometry.  H_q must be a multiple of H_kv (query head h reads KV
  *   head h / (H_q/H_kv)).  D is 64 or 128.  N_max <= 64.
+ *   All kv_capacity slots of every request of a contiguous cache must be readable memory: the
+ *   attention call may fetch slots past prefix_len + num_nodes (it never uses what they hold).
  */
 typedef struct specvlm_attn_desc {
     int32_t dtype;                 /* specvlm_dtype */
