@@ -72,7 +72,7 @@ constexpr int kTile = 32;           // keys per tile
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kTau = 8.0f;        // log2 of how far a probability may exceed 1 before the reference max moves
-constexpr size_t kCounterAlign = 256;
+constexpr int kMaxSplitHeads = 4096;  // (request, head) pairs a split call can have: one set of ticket counters each
 
 struct MfmaParams {
     KvGeom g;
@@ -731,6 +731,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
 // is slower; workgroups beyond 256 run as further rounds.  The cache capacity stands in for
 // the request lengths, which the host does not know.
 int32_t attn_mfma_pick_splits(const specvlm_attn_desc& d) {
+    const int64_t heads = static_cast<int64_t>(d.B) * d.H_q;
+    if (heads > kMaxSplitHeads) return 1;      // more (request, head) pairs than ticket counters: that many fill the chip unsplit
     if (d.num_splits > 0) return min(d.num_splits, 64);
     const int cus = 256;
     const int bh = d.B * d.H_q;
@@ -757,10 +759,10 @@ int32_t attn_mfma_pick_splits(const specvlm_attn_desc& d) {
     return best;
 }
 
-static size_t counter_bytes(const specvlm_attn_desc& d) {
-    const size_t raw = static_cast<size_t>(d.B) * d.H_q * 4 * sizeof(int32_t);
-    return (raw + kCounterAlign - 1) / kCounterAlign * kCounterAlign;
-}
+// The ticket counters occupy a region of fixed size at the start of the workspace, whatever the
+// shape: a later call of another shape then finds its counters where every earlier call left
+// zeros, never where one stored partial results.
+static size_t counter_bytes(const specvlm_attn_desc&) { return kMaxSplitHeads * 4 * sizeof(int32_t); }
 
 size_t attn_mfma_workspace_bytes(const specvlm_attn_desc& d) {
     const int splits = attn_mfma_pick_splits(d);

@@ -91,7 +91,7 @@ def test_split_choice_and_workspace_sizes_for_the_five_workloads():
         need = lib.specvlm_tree_verify_attn_workspace_bytes(ctypes.byref(d))
         if d.dtype == 0 and want > 1:
             parts = d.B * d.H_q * want
-            counters = -(-d.B * d.H_q * 4 * 4 // 256) * 256
+            counters = 4096 * 4 * 4                                              # a fixed region, whatever the shape
             assert need == counters + parts * (64 * d.D * 2 + 64 * 8), name     # bf16 partials + (max, sum) pairs
     d = cases["C3"][0]
     d.num_splits = 5                                                             # a caller's choice is kept

@@ -204,6 +204,26 @@ def test_one_workspace_across_shapes_and_graph_replays(sv, oracle):
         assert_attn_close(to_host_f64(out), ref, "bf16", f"replay {rep}")
 
 
+def test_one_workspace_across_head_counts(sv, oracle):
+    """Split calls with 4, 64 and 36 (request, head) pairs alternate on one workspace that was
+    zero-filled once: where one call keeps its arrival tickets another must never have stored partial
+    results, and every call leaves the ticket region zero."""
+    from gpu_util import random_case, i32, to_dev, to_host_f64, assert_attn_close
+    cases = [random_case(84, "bf16", B=1, Hq=4, Hkv=2, D=128, N_max=60, P_list=[400]),
+             random_case(85, "bf16", B=2, Hq=32, Hkv=8, D=128, N_max=33, P_list=[150, 260]),
+             random_case(86, "bf16", B=3, Hq=12, Hkv=12, D=64, N_max=64, P_list=[90, 0, 310])]
+    refs = [oracle.tree_attn(c["q"], c["k"], c["v"], c["prefix_len"], c["parent"])[0] for c in cases]
+    dev = [tuple(to_dev(c[x]) for x in ("q", "k", "v")) + (i32(c["prefix_len"]), i32(c["parent"])) for c in cases]
+    ws = torch.zeros(1 << 24, dtype=torch.uint8, device="cuda")
+    order = [(0, 8), (1, 3), (0, 5), (2, 4), (1, 8), (2, 2), (0, 3), (1, 2)]
+    for rnd in range(2):
+        for ci, splits in order:
+            q, k, v, P, par = dev[ci]
+            out = sv.specvlm_tree_verify_attn(q, k, v, P, par, workspace=ws, num_splits=splits)
+            assert_attn_close(to_host_f64(out), refs[ci], "bf16", f"round {rnd} case {ci} splits {splits}")
+            assert int(ws[:4096 * 16].view(torch.int32).abs().max()) == 0, "ticket region not left zero"
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_random_shapes_sweep(sv, oracle, seed):
     """Seeded random geometry: batch, grouped heads, head size, node counts, prefix lengths from
