@@ -142,6 +142,27 @@ int32_t specvlm_tree_verify_attn(const specvlm_attn_desc *desc,
                                  int32_t *err_flag_dev, void *stream);
 
 /*
+ * specvlm_tree_verify_attn for callers that cannot allocate device memory or carry a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and error reporting, without workspace_dev/workspace_bytes: the scratch is a
+ * static device array inside the library, SPECVLM_STATIC_WORKSPACE_BYTES long, one per GPU, held
+ * from the moment the library is loaded on that GPU until the process ends.  The call allocates
+ * and frees nothing (the first call on a device asks the runtime once for the array's address).
+ * A shape whose specvlm_tree_verify_attn_workspace_bytes exceeds the array returns
+ * SPECVLM_WORKSPACE_TOO_SMALL and launches nothing.  Every call on a GPU uses that GPU's one
+ * array: calls that may overlap on one GPU (two streams) race on it and must use
+ * specvlm_tree_verify_attn with workspaces of their own instead; calls ordered by a stream, or
+ * replays of a captured graph, are fine.  The device must be the current one at the call.
+ */
+#define SPECVLM_STATIC_WORKSPACE_BYTES (16u << 20)
+int32_t specvlm_tree_verify_attn_static(const specvlm_attn_desc *desc,
+                                        const void *q_dev, const void *k_cache_dev, const void *v_cache_dev,
+                                        const int32_t *block_table_dev, const int32_t *prefix_len_dev,
+                                        const int32_t *num_nodes_dev, const int32_t *parent_dev,
+                                        void *o_dev, float *lse_dev,
+                                        int32_t *err_flag_dev, void *stream);
+
+/*
  * Greedy target token per tree node (temperature 0, Sec. 4.1):
  *     amax[b,i] = the LOWEST v with logits[b,i,v] == max_v' logits[b,i,v']
  * (values compare as real numbers, -0 == +0; precondition: no NaN; an all -inf

@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     specvlm_tree_accept_sample,
     specvlm_tree_verify_attn,
     specvlm_tree_verify_attn_num_splits,
+    specvlm_tree_verify_attn_static,
     specvlm_tree_verify_attn_workspace_bytes,
     specvlm_version,
     specvlm_visual_pool,

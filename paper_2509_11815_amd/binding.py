@@ -19,7 +19,7 @@ ERR_BITS = {1: "BAD_PARENT", 2: "BAD_NUM_NODES", 4: "BAD_LENGTH", 8: "PATH_TOO_L
 
 EXPORTS = ["specvlm_version", "specvlm_last_hip_error", "specvlm_tree_verify_attn_workspace_bytes",
            "specvlm_tree_verify_attn_num_splits",
-           "specvlm_tree_verify_attn", "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_tree_accept_sample",
+           "specvlm_tree_verify_attn", "specvlm_tree_verify_attn_static", "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_tree_accept_sample",
            "specvlm_kv_compact", "specvlm_draft_topk", "specvlm_draft_topk_select", "specvlm_draft_select",
            "specvlm_draft_finalize",
            "specvlm_head_argmax", "specvlm_head_argmax_workspace_bytes",
@@ -64,6 +64,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.specvlm_tree_verify_attn_num_splits.argtypes = [ctypes.POINTER(AttnDesc)]
     L.specvlm_tree_verify_attn.restype = i32
     L.specvlm_tree_verify_attn.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 9 + [vp, ctypes.c_size_t, vp, vp]
+    L.specvlm_tree_verify_attn_static.restype = i32
+    L.specvlm_tree_verify_attn_static.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 9 + [vp, vp]
     L.specvlm_node_argmax.restype = i32
     L.specvlm_node_argmax.argtypes = [i32, i32, i32, i32, vp, i64, i64, vp, vp, vp]
     L.specvlm_tree_accept.restype = i32
@@ -190,6 +192,24 @@ def specvlm_tree_verify_attn(q, k_cache, v_cache, prefix_len, parent, *, num_nod
         _ptr(_dev_i32(parent, "parent")), _ptr(out), _ptr(lse), _ptr(workspace), ctypes.c_size_t(wbytes),
         _ptr(err_flag), _stream(stream))
     _check(rc, "specvlm_tree_verify_attn")
+    return out
+
+
+def specvlm_tree_verify_attn_static(q, k_cache, v_cache, prefix_len, parent, *, out, num_nodes=None,
+                                    block_table=None, lse=None, err_flag=None, softmax_scale=0.0,
+                                    num_splits=0, desc=None, stream=None):
+    """specvlm_tree_verify_attn on the library's own static scratch array.  Allocates nothing: `out`
+    (and `lse`) must be supplied."""
+    if desc is None:
+        desc = make_attn_desc(q, k_cache, out, block_table=block_table, softmax_scale=softmax_scale,
+                              num_splits=num_splits)
+    if k_cache.stride() != v_cache.stride() or k_cache.shape != v_cache.shape:
+        raise ValueError("K and V caches must share one geometry")
+    rc = lib().specvlm_tree_verify_attn_static(
+        ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(_dev_i32(block_table, "block_table")),
+        _ptr(_dev_i32(prefix_len, "prefix_len")), _ptr(_dev_i32(num_nodes, "num_nodes")),
+        _ptr(_dev_i32(parent, "parent")), _ptr(out), _ptr(lse), _ptr(err_flag), _stream(stream))
+    _check(rc, "specvlm_tree_verify_attn_static")
     return out
 
 

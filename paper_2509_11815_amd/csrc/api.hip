@@ -66,12 +66,12 @@ int32_t specvlm_tree_verify_attn_num_splits(const specvlm_attn_desc* desc) {
     return attn_mfma_pick_splits(*desc);
 }
 
-int32_t specvlm_tree_verify_attn(const specvlm_attn_desc* desc, const void* q_dev, const void* k_cache_dev,
-                                 const void* v_cache_dev, const int32_t* block_table_dev,
-                                 const int32_t* prefix_len_dev, const int32_t* num_nodes_dev,
-                                 const int32_t* parent_dev, void* o_dev, float* lse_dev,
-                                 void* workspace_dev, size_t workspace_bytes, int32_t* err_flag_dev,
-                                 void* stream) {
+static int32_t tree_verify_attn(const specvlm_attn_desc* desc, const void* q_dev, const void* k_cache_dev,
+                                const void* v_cache_dev, const int32_t* block_table_dev,
+                                const int32_t* prefix_len_dev, const int32_t* num_nodes_dev,
+                                const int32_t* parent_dev, void* o_dev, float* lse_dev, bool static_workspace,
+                                void* workspace_dev, size_t workspace_bytes, int32_t* err_flag_dev,
+                                void* stream) {
     if (!desc) return SPECVLM_INVALID_ARG;
     int32_t rc = check_attn_desc(*desc);
     if (rc) return rc;
@@ -94,10 +94,35 @@ int32_t specvlm_tree_verify_attn(const specvlm_attn_desc* desc, const void* q_de
     if (desc->num_splits == 1000) return launch_attn_valu(a);
     const size_t need = attn_mfma_workspace_bytes(*desc);
     if (attn_mfma_pick_splits(*desc) > 1) {
-        if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255u)) return SPECVLM_INVALID_ARG;
-        if (workspace_bytes < need) return SPECVLM_WORKSPACE_TOO_SMALL;
+        if (static_workspace) {
+            if (need > SPECVLM_STATIC_WORKSPACE_BYTES) return SPECVLM_WORKSPACE_TOO_SMALL;
+            rc = attn_static_workspace(&a.workspace);
+            if (rc) return rc;
+            a.workspace_bytes = SPECVLM_STATIC_WORKSPACE_BYTES;
+        }
+        if (!a.workspace || (reinterpret_cast<uintptr_t>(a.workspace) & 255u)) return SPECVLM_INVALID_ARG;
+        if (a.workspace_bytes < need) return SPECVLM_WORKSPACE_TOO_SMALL;
     }
     return launch_attn_mfma(a);
+}
+
+int32_t specvlm_tree_verify_attn(const specvlm_attn_desc* desc, const void* q_dev, const void* k_cache_dev,
+                                 const void* v_cache_dev, const int32_t* block_table_dev,
+                                 const int32_t* prefix_len_dev, const int32_t* num_nodes_dev,
+                                 const int32_t* parent_dev, void* o_dev, float* lse_dev,
+                                 void* workspace_dev, size_t workspace_bytes, int32_t* err_flag_dev,
+                                 void* stream) {
+    return tree_verify_attn(desc, q_dev, k_cache_dev, v_cache_dev, block_table_dev, prefix_len_dev, num_nodes_dev,
+                            parent_dev, o_dev, lse_dev, false, workspace_dev, workspace_bytes, err_flag_dev, stream);
+}
+
+int32_t specvlm_tree_verify_attn_static(const specvlm_attn_desc* desc, const void* q_dev, const void* k_cache_dev,
+                                        const void* v_cache_dev, const int32_t* block_table_dev,
+                                        const int32_t* prefix_len_dev, const int32_t* num_nodes_dev,
+                                        const int32_t* parent_dev, void* o_dev, float* lse_dev,
+                                        int32_t* err_flag_dev, void* stream) {
+    return tree_verify_attn(desc, q_dev, k_cache_dev, v_cache_dev, block_table_dev, prefix_len_dev, num_nodes_dev,
+                            parent_dev, o_dev, lse_dev, true, nullptr, 0, err_flag_dev, stream);
 }
 
 int32_t specvlm_node_argmax(int32_t dtype, int32_t B, int32_t N_max, int32_t V, const void* logits_dev,

@@ -42,6 +42,8 @@
 //             workspace with write-through stores, and for every query block the last
 //             split to arrive -- found with a ticket counter per (request, head, query
 //             block) -- merges the splits, adding a split up while the next ones still load
+#include <atomic>
+
 #include "common.hpp"
 
 namespace specvlm {
@@ -769,6 +771,34 @@ size_t attn_mfma_workspace_bytes(const specvlm_attn_desc& d) {
     if (splits == 1) return 0;
     const size_t parts = static_cast<size_t>(d.B) * d.H_q * splits;
     return counter_bytes(d) + parts * (static_cast<size_t>(kQRows) * d.D * 2 + kQRows * 8);
+}
+
+// ---- library-owned scratch for callers that cannot allocate device memory -----------------------
+// One array per GPU (each device holds its own copy of the code object's globals, zero when the
+// object is loaded).  Host code must not use the array's name as an address: the device address
+// is asked for once per device and kept.
+static __device__ __align__(256) unsigned char scratch[SPECVLM_STATIC_WORKSPACE_BYTES];
+
+int32_t attn_static_workspace(void** ptr_out) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> ptr_of_device[kMaxDevices];
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        note_hip_error(e != hipSuccess ? e : hipErrorInvalidDevice);
+        return SPECVLM_HIP_ERROR;
+    }
+    void* ptr = ptr_of_device[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));         // this device's copy (the current device)
+        if (e != hipSuccess || !ptr) {
+            note_hip_error(e != hipSuccess ? e : hipErrorInvalidSymbol);
+            return SPECVLM_HIP_ERROR;
+        }
+        ptr_of_device[dev].store(ptr, std::memory_order_release);   // two threads racing here store the same address
+    }
+    *ptr_out = ptr;
+    return SPECVLM_OK;
 }
 
 int32_t launch_attn_mfma(const AttnArgs& a) {

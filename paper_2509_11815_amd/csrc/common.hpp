@@ -126,5 +126,7 @@ int32_t launch_attn_valu(const AttnArgs& a);
 int32_t launch_attn_mfma(const AttnArgs& a);
 size_t attn_mfma_workspace_bytes(const specvlm_attn_desc& d);
 int32_t attn_mfma_pick_splits(const specvlm_attn_desc& d);
+// Device address of the current device's library-owned scratch array (SPECVLM_STATIC_WORKSPACE_BYTES).
+int32_t attn_static_workspace(void** ptr_out);
 
 }  // namespace specvlm
