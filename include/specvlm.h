@@ -56,6 +56,7 @@ typedef enum specvlm_dtype {
 
 #define SPECVLM_MAX_NODES 64
 #define SPECVLM_PAGE_SIZE 16
+#define SPECVLM_MAX_SPLITS 64        /* key-range splits per (request, head) */
 #define SPECVLM_MAX_CANDIDATES 8192  /* draft growth: scored candidates per request */
 
 /*
@@ -69,8 +70,10 @@ typedef enum specvlm_dtype {
  *              (logical slot s of request b lives in block block_table[b][s/16], row s%16).
  *   K and V share one geometry.  H_q must be a multiple of H_kv (query head h reads KV
  *   head h / (H_q/H_kv)).  D is 64 or 128.  N_max <= 64.
- *   All kv_capacity slots of every request of a contiguous cache must be readable memory: the
- *   attention call may fetch slots past prefix_len + num_nodes (it never uses what they hold).
+ *   All kv_capacity slots of every request of a contiguous cache, and every block of a paged pool
+ *   that a block table names, must be readable memory: the attention call may FETCH slots past
+ *   prefix_len + num_nodes (up to kv_capacity; paged: up to the end of the request's last block);
+ *   it never USES what they hold, whatever bit patterns are there.
  */
 typedef struct specvlm_attn_desc {
     int32_t dtype;                 /* specvlm_dtype */
@@ -81,7 +84,9 @@ typedef struct specvlm_attn_desc {
     int32_t max_blocks_per_req;    /* second dimension of block_table (paged only) */
     int32_t num_blocks;            /* physical blocks in the pool (paged only)     */
     int32_t kv_capacity;           /* slots per request (contiguous); paged: max_blocks_per_req*16 */
-    int32_t num_splits;            /* key-range splits per (request, head); 0 lets the library choose */
+    int32_t num_splits;            /* key-range splits per (request, head): 0 lets the library choose, 1 ..
+                                      SPECVLM_MAX_SPLITS is taken as given (anything else: SPECVLM_INVALID_ARG);
+                                      with more than 4096 (request, head) pairs a call always runs unsplit */
     int64_t q_stride_b, q_stride_n, q_stride_h;
     int64_t o_stride_b, o_stride_n, o_stride_h;
     int64_t kv_stride_b, kv_stride_h, kv_stride_t;
@@ -97,9 +102,10 @@ int32_t specvlm_last_hip_error(void);
  * Scratch bytes specvlm_tree_verify_attn needs for `desc` (arrival counters and split-key
  * partial results; 0 when the shape needs none).  Returns 0 when desc is invalid.  The
  * workspace is device memory, 256-byte aligned.  It must be ZERO-FILLED ONCE after
- * allocation; every call leaves its counter words zero again, so the same workspace can
- * be reused by later calls (of any shape it is large enough for) without clearing.  Two
- * calls that may run concurrently need separate workspaces.
+ * allocation; every call leaves its counter words zero again, and the counters occupy the
+ * same fixed region at the start whatever the shape, so the same workspace can be reused by
+ * later calls (of any shape it is large enough for) without clearing.  Two calls that may
+ * run concurrently need separate workspaces.
  */
 size_t specvlm_tree_verify_attn_workspace_bytes(const specvlm_attn_desc *desc);
 
@@ -111,9 +117,10 @@ size_t specvlm_tree_verify_attn_workspace_bytes(const specvlm_attn_desc *desc);
 int32_t specvlm_tree_verify_attn_num_splits(const specvlm_attn_desc *desc);
 
 /*
- * Tree-masked verification attention for ONE layer (Sec. 3.1 "verifies ... in a
- * single forward pass", Sec. 4.1 "tree attention"; Sec. 3.2: the whole KV cache
- * is streamed from HBM once per step).  For request b, query head h and tree
+ * Tree-masked verification attention for ONE layer (Sec. 3.1: the target checks all drafted
+ * tokens of a round in one forward pass; Sec. 4.1: the drafted tokens form a tree and the
+ * pass uses tree attention; Sec. 3.2: the whole KV cache is streamed from HBM once per
+ * step).  For request b, query head h and tree
  * node i < num_nodes[b]:
  *     J(i) = {0 .. prefix_len[b]-1}  U  {prefix_len[b] + j : j is i or an ancestor of i}
  *     o[b,i,h,:] = softmax_{j in J(i)}(scale * q[b,i,h,:] . K[b,kv(h),j,:]) . V[b,kv(h),j,:]
@@ -121,7 +128,9 @@ int32_t specvlm_tree_verify_attn_num_splits(const specvlm_attn_desc *desc);
  * Precondition: the caller has already written the tree tokens' K/V rows into
  * logical slots [prefix_len[b], prefix_len[b]+num_nodes[b]) of the cache, with
  * position encoding applied.  Rows i >= num_nodes[b] of o / lse are not written.
- * Slots at or beyond prefix_len[b]+num_nodes[b] are never read.
+ * Slots at or beyond prefix_len[b]+num_nodes[b] may be fetched (see the geometry note
+ * above) but never influence a result.  A block table entry outside [0, num_blocks)
+ * sets SPECVLM_ERR_BAD_BLOCK (memory outside the pool is still never touched).
  *
  *   q_dev, o_dev         device, desc->dtype, geometry from desc; 16-byte aligned rows
  *   k_cache_dev, v_cache_dev  device, desc->dtype, read-only here
@@ -161,6 +170,21 @@ int32_t specvlm_tree_verify_attn_static(const specvlm_attn_desc *desc,
                                         const int32_t *num_nodes_dev, const int32_t *parent_dev,
                                         void *o_dev, float *lse_dev,
                                         int32_t *err_flag_dev, void *stream);
+
+/*
+ * Measurement aid, not part of the verification path: the same operation and arguments as
+ * specvlm_tree_verify_attn_static, computed by the vector-ALU kernel that serves SPECVLM_F32
+ * (one workgroup per (request, head, node), no matrix cores, no key-range splits, no scratch)
+ * also when desc->dtype is SPECVLM_BF16.  It exists so that the choice of the matrix-core kernel
+ * for bf16 can be re-measured on the same inputs (bench.py --vector-alu-evidence); results
+ * agree with specvlm_tree_verify_attn within the bf16 tolerance.
+ */
+int32_t specvlm_tree_verify_attn_vector_alu(const specvlm_attn_desc *desc,
+                                            const void *q_dev, const void *k_cache_dev, const void *v_cache_dev,
+                                            const int32_t *block_table_dev, const int32_t *prefix_len_dev,
+                                            const int32_t *num_nodes_dev, const int32_t *parent_dev,
+                                            void *o_dev, float *lse_dev,
+                                            int32_t *err_flag_dev, void *stream);
 
 /*
  * Greedy target token per tree node (temperature 0, Sec. 4.1):
@@ -256,17 +280,22 @@ int32_t specvlm_tree_accept_sample(int32_t dtype, int32_t B, int32_t N_max, int3
  * and kv_stride_* are used.  new_prefix_len_dev may alias prefix_len_dev (that costs a second,
  * tiny launch: the old lengths may only be overwritten after every workgroup has read them).
  *   moved_idx_dev  optional int32 [B, path_cap, 2]: (src_slot, dst_slot) per j, -1 padded.
+ *   err_flag_dev   device int32 or NULL.  A move whose source or destination block id (paged) is
+ *                  outside [0, num_blocks) is NOT made -- nothing is ever written into a block the
+ *                  table does not validly name -- and sets SPECVLM_ERR_BAD_BLOCK.
  */
 int32_t specvlm_kv_compact(const specvlm_attn_desc *desc, int32_t L,
                            void *k_base_dev, void *v_base_dev, int64_t layer_stride,
                            void *const *k_layer_ptrs_dev, void *const *v_layer_ptrs_dev,
                            const int32_t *block_table_dev, const int32_t *prefix_len_dev,
                            const int32_t *path_dev, int32_t path_cap, const int32_t *accept_len_dev,
-                           int32_t *new_prefix_len_dev, int32_t *moved_idx_dev, void *stream);
+                           int32_t *new_prefix_len_dev, int32_t *moved_idx_dev, int32_t *err_flag_dev,
+                           void *stream);
 
 /*
- * Parameter-free visual token compressors (Sec. 3.3: "Pruning drops tokens at random", pooling is a
- * vanilla operator; Table 4: ratios 2x .. 30x).  They shorten the visual prefix the DRAFT reads;
+ * Parameter-free visual token compressors (Sec. 3.4, the elastic vision compressor's two
+ * parameter-free experts: the pruning expert discards a random subset of the visual tokens, the
+ * pooling expert is a plain pooling operator; Table 4: ratios 2x .. 30x).  They shorten the visual prefix the DRAFT reads;
  * the target keeps the full sequence (that is what keeps decoding lossless).  The paper fixes
  * neither the pooling window nor the treatment of a ragged tail; here: average pooling along the
  * token sequence, window = stride = ratio, the last window shorter when the length is not a multiple:

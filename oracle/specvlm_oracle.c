@@ -556,8 +556,8 @@ int oracle_tree_finalize(int B, int C, int N_max, const float *cand_score, const
 }
 
 /*
- * ---- parameter-free visual token compressors (Sec. 3.3: "Pruning drops tokens at random; Pooling
- * [is a] vanilla" operator; Table 4 uses ratios 2x .. 30x) ------------------------------------------
+ * ---- parameter-free visual token compressors (Sec. 3.4, the elastic vision compressor:
+ * pruning discards a random subset of the tokens, pooling is a plain operator; Table 4 uses ratios 2x .. 30x) ------------------------------------------
  * They shorten the visual prefix the DRAFT reads (the target keeps the full sequence, which is what
  * keeps decoding lossless).  The paper fixes neither the pooling window nor what happens to a ragged
  * tail; the reading here: average pooling along the token sequence with window = stride = ratio, the

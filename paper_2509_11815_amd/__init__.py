@@ -7,6 +7,7 @@ PyTorch is used for device memory and streams only.
 from .binding import (  # noqa: F401
     AttnDesc,
     SpecvlmError,
+    err_flag_names,
     lib,
     load_library,
     specvlm_draft_finalize,
@@ -23,6 +24,7 @@ from .binding import (  # noqa: F401
     specvlm_tree_verify_attn,
     specvlm_tree_verify_attn_num_splits,
     specvlm_tree_verify_attn_static,
+    specvlm_tree_verify_attn_vector_alu,
     specvlm_tree_verify_attn_workspace_bytes,
     specvlm_version,
     specvlm_visual_pool,

@@ -15,11 +15,19 @@ from . import build as _build
 
 SPECVLM_BF16, SPECVLM_F32 = 0, 1
 STATUS = {0: "OK", 1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE_TOO_SMALL", 4: "HIP_ERROR"}
-ERR_BITS = {1: "BAD_PARENT", 2: "BAD_NUM_NODES", 4: "BAD_LENGTH", 8: "PATH_TOO_LONG", 16: "BAD_BLOCK"}
+ERR_BITS = {1: "BAD_PARENT", 2: "BAD_NUM_NODES", 4: "BAD_LENGTH", 8: "PATH_TOO_LONG", 16: "BAD_BLOCK",
+            32: "BAD_TOKEN", 64: "TREE_NOT_CLOSED"}
+
+
+def err_flag_names(word: int) -> list[str]:
+    """Names of the SPECVLM_ERR_* bits set in a device error word (after the caller synchronised)."""
+    return [name for bit, name in ERR_BITS.items() if word & bit] + (
+        [hex(word & ~sum(ERR_BITS))] if word & ~sum(ERR_BITS) else [])
 
 EXPORTS = ["specvlm_version", "specvlm_last_hip_error", "specvlm_tree_verify_attn_workspace_bytes",
            "specvlm_tree_verify_attn_num_splits",
-           "specvlm_tree_verify_attn", "specvlm_tree_verify_attn_static", "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_tree_accept_sample",
+           "specvlm_tree_verify_attn", "specvlm_tree_verify_attn_static", "specvlm_tree_verify_attn_vector_alu",
+           "specvlm_node_argmax", "specvlm_tree_accept", "specvlm_tree_accept_sample",
            "specvlm_kv_compact", "specvlm_draft_topk", "specvlm_draft_topk_select", "specvlm_draft_select",
            "specvlm_draft_finalize",
            "specvlm_head_argmax", "specvlm_head_argmax_workspace_bytes",
@@ -55,6 +63,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
         raise SpecvlmError(f"{path} is missing: build it with `python -m paper_2509_11815_amd.build` "
                            "(there is no fallback path)")
     L = ctypes.CDLL(path)
+    missing = [name for name in EXPORTS if not hasattr(L, name)]
+    if missing:
+        raise SpecvlmError(f"{path} does not export {missing}: rebuild it with `python -m paper_2509_11815_amd.build`")
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     L.specvlm_version.restype = i32
     L.specvlm_last_hip_error.restype = i32
@@ -73,7 +84,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     L.specvlm_tree_accept_sample.restype = i32
     L.specvlm_tree_accept_sample.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, i64, i64, vp, ctypes.c_float] + [vp] * 8
     L.specvlm_kv_compact.restype = i32
-    L.specvlm_kv_compact.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, vp, i64, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    L.specvlm_kv_compact.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, vp, i64, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+    L.specvlm_tree_verify_attn_vector_alu.restype = i32
+    L.specvlm_tree_verify_attn_vector_alu.argtypes = [ctypes.POINTER(AttnDesc)] + [vp] * 9 + [vp, vp]
     L.specvlm_draft_topk.restype = i32
     L.specvlm_draft_topk.argtypes = [i32] * 5 + [vp, i64, i64, vp, i64, vp, i64, vp, vp, vp, i64, vp, vp]
     L.specvlm_draft_topk_select.restype = i32
@@ -195,9 +208,15 @@ def specvlm_tree_verify_attn(q, k_cache, v_cache, prefix_len, parent, *, num_nod
     return out
 
 
+def specvlm_tree_verify_attn_vector_alu(q, k_cache, v_cache, prefix_len, parent, *, out, **kw):
+    """Measurement aid: the same call computed by the vector-ALU kernel (see the header)."""
+    return specvlm_tree_verify_attn_static(q, k_cache, v_cache, prefix_len, parent, out=out,
+                                           _entry="specvlm_tree_verify_attn_vector_alu", **kw)
+
+
 def specvlm_tree_verify_attn_static(q, k_cache, v_cache, prefix_len, parent, *, out, num_nodes=None,
                                     block_table=None, lse=None, err_flag=None, softmax_scale=0.0,
-                                    num_splits=0, desc=None, stream=None):
+                                    num_splits=0, desc=None, stream=None, _entry="specvlm_tree_verify_attn_static"):
     """specvlm_tree_verify_attn on the library's own static scratch array.  Allocates nothing: `out`
     (and `lse`) must be supplied."""
     if desc is None:
@@ -205,11 +224,11 @@ def specvlm_tree_verify_attn_static(q, k_cache, v_cache, prefix_len, parent, *, 
                               num_splits=num_splits)
     if k_cache.stride() != v_cache.stride() or k_cache.shape != v_cache.shape:
         raise ValueError("K and V caches must share one geometry")
-    rc = lib().specvlm_tree_verify_attn_static(
+    rc = getattr(lib(), _entry)(
         ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(_dev_i32(block_table, "block_table")),
         _ptr(_dev_i32(prefix_len, "prefix_len")), _ptr(_dev_i32(num_nodes, "num_nodes")),
         _ptr(_dev_i32(parent, "parent")), _ptr(out), _ptr(lse), _ptr(err_flag), _stream(stream))
-    _check(rc, "specvlm_tree_verify_attn_static")
+    _check(rc, _entry)
     return out
 
 
@@ -279,7 +298,7 @@ def specvlm_tree_accept_sample(parent, draft_tok, logits, u_accept, u_bonus, *, 
 
 
 def specvlm_kv_compact(k_caches, v_caches, prefix_len, path, accept_len, *, block_table=None,
-                       new_prefix_len=None, moved_idx=None, layer_ptrs=None, stream=None):
+                       new_prefix_len=None, moved_idx=None, layer_ptrs=None, err_flag=None, stream=None):
     """In-place compaction.  k_caches/v_caches: one tensor [L, <per-layer cache dims>] (layer stride taken
     from the tensor), or with `layer_ptrs=(k_ptrs, v_ptrs)` (int64 device tensors of L addresses) a single
     layer's tensor that only provides the geometry.  Returns (new_prefix_len, moved_idx)."""
@@ -315,7 +334,7 @@ def specvlm_kv_compact(k_caches, v_caches, prefix_len, path, accept_len, *, bloc
                                   _ptr(_dev_i32(block_table, "block_table")),
                                   _ptr(_dev_i32(prefix_len, "prefix_len")), _ptr(_dev_i32(path, "path")),
                                   path_cap, _ptr(_dev_i32(accept_len, "accept_len")), _ptr(new_prefix_len),
-                                  _ptr(moved_idx), _stream(stream))
+                                  _ptr(moved_idx), _ptr(err_flag), _stream(stream))
     _check(rc, "specvlm_kv_compact")
     return new_prefix_len, moved_idx
 

@@ -35,7 +35,7 @@ static int32_t check_attn_desc(const specvlm_attn_desc& d) {
     if (d.H_q < 1 || d.H_q % d.H_kv) return SPECVLM_INVALID_ARG;
     if (d.N_max < 1 || d.N_max > SPECVLM_MAX_NODES) return SPECVLM_INVALID_ARG;
     if (!(d.softmax_scale >= 0.f) || isinf(d.softmax_scale)) return SPECVLM_INVALID_ARG;
-    if (d.num_splits < 0) return SPECVLM_INVALID_ARG;
+    if (d.num_splits < 0 || d.num_splits > SPECVLM_MAX_SPLITS) return SPECVLM_INVALID_ARG;
     const int vec = d.dtype == SPECVLM_BF16 ? 8 : 4;
     const int64_t st[6] = {d.q_stride_b, d.q_stride_n, d.q_stride_h, d.o_stride_b, d.o_stride_n, d.o_stride_h};
     for (int64_t s : st)
@@ -62,16 +62,19 @@ size_t specvlm_tree_verify_attn_workspace_bytes(const specvlm_attn_desc* desc) {
 
 int32_t specvlm_tree_verify_attn_num_splits(const specvlm_attn_desc* desc) {
     if (!desc || check_attn_desc(*desc)) return 0;
-    if (desc->dtype == SPECVLM_F32 || desc->num_splits == 1000) return 1;
+    if (desc->dtype == SPECVLM_F32) return 1;
     return attn_mfma_pick_splits(*desc);
 }
+
+enum { kCallerWorkspace = 0, kStaticWorkspace = 1, kVectorAluKernel = 2 };
 
 static int32_t tree_verify_attn(const specvlm_attn_desc* desc, const void* q_dev, const void* k_cache_dev,
                                 const void* v_cache_dev, const int32_t* block_table_dev,
                                 const int32_t* prefix_len_dev, const int32_t* num_nodes_dev,
-                                const int32_t* parent_dev, void* o_dev, float* lse_dev, bool static_workspace,
+                                const int32_t* parent_dev, void* o_dev, float* lse_dev, int mode,
                                 void* workspace_dev, size_t workspace_bytes, int32_t* err_flag_dev,
                                 void* stream) {
+    const bool static_workspace = mode == kStaticWorkspace;
     if (!desc) return SPECVLM_INVALID_ARG;
     int32_t rc = check_attn_desc(*desc);
     if (rc) return rc;
@@ -88,10 +91,7 @@ static int32_t tree_verify_attn(const specvlm_attn_desc* desc, const void* q_dev
     a.parent = parent_dev; a.o = o_dev; a.lse = lse_dev;
     a.workspace = workspace_dev; a.workspace_bytes = workspace_bytes;
     a.err_flag = err_flag_dev; a.stream = static_cast<hipStream_t>(stream);
-    if (desc->dtype == SPECVLM_F32) return launch_attn_valu(a);
-    // num_splits < 0 is rejected above; the special value 1000 selects the bf16 VALU kernel,
-    // kept only to measure what the vector ALUs reach on this step.
-    if (desc->num_splits == 1000) return launch_attn_valu(a);
+    if (desc->dtype == SPECVLM_F32 || mode == kVectorAluKernel) return launch_attn_valu(a);
     const size_t need = attn_mfma_workspace_bytes(*desc);
     if (attn_mfma_pick_splits(*desc) > 1) {
         if (static_workspace) {
@@ -113,7 +113,7 @@ int32_t specvlm_tree_verify_attn(const specvlm_attn_desc* desc, const void* q_de
                                  void* workspace_dev, size_t workspace_bytes, int32_t* err_flag_dev,
                                  void* stream) {
     return tree_verify_attn(desc, q_dev, k_cache_dev, v_cache_dev, block_table_dev, prefix_len_dev, num_nodes_dev,
-                            parent_dev, o_dev, lse_dev, false, workspace_dev, workspace_bytes, err_flag_dev, stream);
+                            parent_dev, o_dev, lse_dev, kCallerWorkspace, workspace_dev, workspace_bytes, err_flag_dev, stream);
 }
 
 int32_t specvlm_tree_verify_attn_static(const specvlm_attn_desc* desc, const void* q_dev, const void* k_cache_dev,
@@ -122,7 +122,16 @@ int32_t specvlm_tree_verify_attn_static(const specvlm_attn_desc* desc, const voi
                                         const int32_t* parent_dev, void* o_dev, float* lse_dev,
                                         int32_t* err_flag_dev, void* stream) {
     return tree_verify_attn(desc, q_dev, k_cache_dev, v_cache_dev, block_table_dev, prefix_len_dev, num_nodes_dev,
-                            parent_dev, o_dev, lse_dev, true, nullptr, 0, err_flag_dev, stream);
+                            parent_dev, o_dev, lse_dev, kStaticWorkspace, nullptr, 0, err_flag_dev, stream);
+}
+
+int32_t specvlm_tree_verify_attn_vector_alu(const specvlm_attn_desc* desc, const void* q_dev, const void* k_cache_dev,
+                                            const void* v_cache_dev, const int32_t* block_table_dev,
+                                            const int32_t* prefix_len_dev, const int32_t* num_nodes_dev,
+                                            const int32_t* parent_dev, void* o_dev, float* lse_dev,
+                                            int32_t* err_flag_dev, void* stream) {
+    return tree_verify_attn(desc, q_dev, k_cache_dev, v_cache_dev, block_table_dev, prefix_len_dev, num_nodes_dev,
+                            parent_dev, o_dev, lse_dev, kVectorAluKernel, nullptr, 0, err_flag_dev, stream);
 }
 
 int32_t specvlm_node_argmax(int32_t dtype, int32_t B, int32_t N_max, int32_t V, const void* logits_dev,
@@ -196,7 +205,8 @@ int32_t specvlm_kv_compact(const specvlm_attn_desc* desc, int32_t L, void* k_bas
                            int64_t layer_stride, void* const* k_layer_ptrs_dev, void* const* v_layer_ptrs_dev,
                            const int32_t* block_table_dev, const int32_t* prefix_len_dev,
                            const int32_t* path_dev, int32_t path_cap, const int32_t* accept_len_dev,
-                           int32_t* new_prefix_len_dev, int32_t* moved_idx_dev, void* stream) {
+                           int32_t* new_prefix_len_dev, int32_t* moved_idx_dev, int32_t* err_flag_dev,
+                           void* stream) {
     if (!desc) return SPECVLM_INVALID_ARG;
     int32_t rc = check_kv_geometry(*desc);
     if (rc) return rc;
@@ -214,7 +224,7 @@ int32_t specvlm_kv_compact(const specvlm_attn_desc* desc, int32_t L, void* k_bas
     }
     return launch_kv_compact(*desc, L, k_base_dev, v_base_dev, layer_stride, k_layer_ptrs_dev,
                              v_layer_ptrs_dev, block_table_dev, prefix_len_dev, path_dev, path_cap,
-                             accept_len_dev, new_prefix_len_dev, moved_idx_dev,
+                             accept_len_dev, new_prefix_len_dev, moved_idx_dev, err_flag_dev,
                              static_cast<hipStream_t>(stream));
 }
 

@@ -317,12 +317,15 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
     // Paged cache: physical ids of the two 16-key blocks of a tile, through the scalar cache.
     // They are looked up one tile ahead of the loads that need them, so the look-up latency
     // never sits between a free ring slot and its refill.
+    bool bad_block = false;                     // uniform per wavefront: an id outside the pool was looked up (and clamped)
     auto fetch_blocks = [&](int j, int (&phys)[2]) {
         if (!p.g.block_table) return;
         const int blk0 = (stream + j * nstream) * (kTile >> 4), last_blk = (S - 1) >> 4;
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
+        for (int x = 0; x < 2; ++x) {
             phys[x] = ((const_i32)p.g.block_table)[static_cast<int64_t>(b) * p.g.max_blocks + min(blk0 + x, last_blk)];
+            bad_block = bad_block || phys[x] < 0 || phys[x] >= p.g.num_blocks;
+        }
     };
     typedef __attribute__((address_space(3))) int lds_int;
     // Next in the queue: the parent array (wavefront 0; lanes past N_max re-read its last entry),
@@ -532,6 +535,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(MfmaParams p) {
         __syncthreads();
     }
 
+    if (bad_block && lane == 0 && p.err_flag) atomicOr(p.err_flag, SPECVLM_ERR_BAD_BLOCK);
     // ---- merge the streams of the workgroup ------------------------------------------------------
     // Query block q4 = QBW*qw + qb (16 rows) is owned by one wavefront of query share qw, chosen
     // so that the four owners (wavefront index kStreams*qw + stream) sit on four different SIMDs.  Every wavefront publishes its reference maxima and sums; the other streams

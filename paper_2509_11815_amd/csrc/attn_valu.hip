@@ -105,10 +105,11 @@ __global__ __launch_bounds__(256) void attn_valu_kernel(ValuParams p) {
     float acc[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) acc[d] = 0.f;
+    bool bad_block = false;
     for (int j = tid; j < S; j += 256) {
         const bool visible = j < P || ((mask >> (j - P)) & 1ull);
         if (!visible) continue;
-        const int64_t off = kv_row_offset(p.g, b, hk, j);
+        const int64_t off = kv_row_offset(p.g, b, hk, j, bad_block);
         float dot = 0.f;
 #pragma unroll
         for (int c = 0; c < D / VEC; ++c) {
@@ -131,6 +132,7 @@ __global__ __launch_bounds__(256) void attn_valu_kernel(ValuParams p) {
         }
         m = m_new;
     }
+    if (bad_block && p.err_flag) atomicOr(p.err_flag, SPECVLM_ERR_BAD_BLOCK);
     // merge the 256 private states: common max, rescale, sum
     float M = m;
 #pragma unroll

@@ -33,9 +33,12 @@ struct KvGeom {
 };
 
 // Element offset of logical slot `slot` of request b, KV head hk.  `slot` must be < capacity.
-__device__ __forceinline__ int64_t kv_row_offset(const KvGeom& g, int b, int hk, int slot) {
+// A block id outside [0, num_blocks) sets `bad_block` (the caller reports SPECVLM_ERR_BAD_BLOCK and
+// must not write there); the offset returned then lies inside the pool all the same.
+__device__ __forceinline__ int64_t kv_row_offset(const KvGeom& g, int b, int hk, int slot, bool& bad_block) {
     if (g.block_table) {
         int blk = g.block_table[static_cast<int64_t>(b) * g.max_blocks + (slot >> 4)];
+        if (blk < 0 || blk >= g.num_blocks) bad_block = true;
         blk = min(max(blk, 0), g.num_blocks - 1);
         return blk * g.stride_b + hk * g.stride_h + (slot & 15) * g.stride_t;
     }
@@ -69,7 +72,7 @@ int32_t launch_kv_compact(const specvlm_attn_desc& d, int32_t L, void* k_base, v
                           int64_t layer_stride, void* const* k_ptrs, void* const* v_ptrs,
                           const int32_t* block_table, const int32_t* prefix_len, const int32_t* path,
                           int32_t path_cap, const int32_t* accept_len, int32_t* new_prefix_len,
-                          int32_t* moved_idx, hipStream_t stream);
+                          int32_t* moved_idx, int32_t* err_flag, hipStream_t stream);
 
 int32_t launch_visual_pool(int32_t dtype, int32_t B, int32_t T, int32_t E, int32_t ratio, const void* x,
                            int64_t x_sb, int64_t x_st, const int32_t* num_tokens, void* y, int64_t y_sb,

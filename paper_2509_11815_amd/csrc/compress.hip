@@ -1,5 +1,6 @@
-// Parameter-free visual token compressors of the draft side (SpecVLM Sec. 3.3: pruning drops
-// tokens at random, pooling is a vanilla operator; Table 4 evaluates ratios 2x .. 30x).  They
+// Parameter-free visual token compressors of the draft side (SpecVLM Sec. 3.4, the elastic
+// vision compressor's parameter-free experts: pruning discards a random subset of the visual tokens,
+// pooling is a plain pooling operator; Table 4 evaluates ratios 2x .. 30x).  They
 // shorten the visual prefix the draft reads; the target keeps the full sequence.
 //
 //   pool   y[b,j,:] = mean of x[b, j*ratio .. min((j+1)*ratio, T_b) - 1, :]   (fp32 sum, one rounding)

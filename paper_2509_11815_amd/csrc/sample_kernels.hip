@@ -309,7 +309,8 @@ __global__ __launch_bounds__(kCompactThreads) void kv_compact_kernel(
     KvGeom g, unsigned char* k_base, unsigned char* v_base, int64_t layer_stride_bytes,
     void* const* k_ptrs, void* const* v_ptrs, int elem_bytes, int row_chunks,
     const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ path, int path_cap,
-    const int32_t* __restrict__ accept_len, int32_t* __restrict__ new_prefix_len, int32_t* __restrict__ moved_idx) {
+    const int32_t* __restrict__ accept_len, int32_t* __restrict__ new_prefix_len, int32_t* __restrict__ moved_idx,
+    int32_t* __restrict__ err_flag) {
     const int l = blockIdx.x >> 1, which = blockIdx.x & 1;
     const int hk = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     // new_prefix_len is given here only when it does not alias prefix_len (which every workgroup
@@ -343,9 +344,15 @@ __global__ __launch_bounds__(kCompactThreads) void kv_compact_kernel(
             const int a = path[b * path_cap + j];
             // a row moves only if it is a valid, different slot inside the cache
             if (a != j && a >= 0 && a < SPECVLM_MAX_NODES && P >= 0 && P + a < g.capacity && P + j < g.capacity) {
-                int64_t src = kv_row_offset(g, b, hk, P + a) * elem_bytes + ch * 16;
-                regs[c] = *reinterpret_cast<const uint4*>(base + src);
-                dst_off[c] = kv_row_offset(g, b, hk, P + j) * elem_bytes + ch * 16;
+                bool bad_block = false;
+                const int64_t src = kv_row_offset(g, b, hk, P + a, bad_block) * elem_bytes + ch * 16;
+                const int64_t dst = kv_row_offset(g, b, hk, P + j, bad_block) * elem_bytes + ch * 16;
+                if (!bad_block) {                      // a row whose block id is out of range stays where it is
+                    regs[c] = *reinterpret_cast<const uint4*>(base + src);
+                    dst_off[c] = dst;
+                } else if (err_flag && ch == 0 && blockIdx.x == 0 && hk == 0) {
+                    atomicOr(err_flag, SPECVLM_ERR_BAD_BLOCK);
+                }
             }
         }
     }
@@ -375,7 +382,7 @@ int32_t launch_kv_compact(const specvlm_attn_desc& d, int32_t L, void* k_base, v
                           int64_t layer_stride, void* const* k_ptrs, void* const* v_ptrs,
                           const int32_t* block_table, const int32_t* prefix_len, const int32_t* path,
                           int32_t path_cap, const int32_t* accept_len, int32_t* new_prefix_len,
-                          int32_t* moved_idx, hipStream_t stream) {
+                          int32_t* moved_idx, int32_t* err_flag, hipStream_t stream) {
     const int eb = d.dtype == SPECVLM_BF16 ? 2 : 4;
     KvGeom g{d.kv_stride_b, d.kv_stride_h, d.kv_stride_t, d.paged ? block_table : nullptr,
              d.max_blocks_per_req, d.num_blocks,
@@ -387,7 +394,7 @@ int32_t launch_kv_compact(const specvlm_attn_desc& d, int32_t L, void* k_base, v
     hipLaunchKernelGGL(kv_compact_kernel, grid, dim3(kCompactThreads), 0, stream, g,
                        static_cast<unsigned char*>(k_base), static_cast<unsigned char*>(v_base),
                        layer_stride * eb, k_ptrs, v_ptrs, eb, d.D * eb / 16, prefix_len, path,
-                       path_cap, accept_len, alias ? nullptr : new_prefix_len, alias ? nullptr : moved_idx);
+                       path_cap, accept_len, alias ? nullptr : new_prefix_len, alias ? nullptr : moved_idx, err_flag);
     int32_t rc = check_launch();
     if (rc || !alias) return rc;
     hipLaunchKernelGGL(kv_compact_finish_kernel, dim3((d.B + 63) / 64), dim3(64), 0, stream, d.B,

@@ -96,6 +96,15 @@ def test_split_choice_and_workspace_sizes_for_the_five_workloads():
     d = cases["C3"][0]
     d.num_splits = 5                                                             # a caller's choice is kept
     assert lib.specvlm_tree_verify_attn_num_splits(ctypes.byref(d)) == 5
+    d.num_splits = 64                                                            # ... up to SPECVLM_MAX_SPLITS
+    assert lib.specvlm_tree_verify_attn_num_splits(ctypes.byref(d)) == 64
+    for bad in (65, 1000, -1):                                                   # outside the documented range 0 .. 64
+        d.num_splits = bad
+        assert lib.specvlm_tree_verify_attn_num_splits(ctypes.byref(d)) == 0
+        assert lib.specvlm_tree_verify_attn_workspace_bytes(ctypes.byref(d)) == 0
+    d.num_splits, d.B, d.H_q, d.H_kv = 8, 33, 128, 128                           # 4224 (request, head) pairs: unsplit
+    assert lib.specvlm_tree_verify_attn_num_splits(ctypes.byref(d)) == 1
+    d.num_splits, d.B, d.H_q, d.H_kv = 0, 1, 32, 32
     assert lib.specvlm_head_argmax_workspace_bytes(1, 60, 32000) == 256 + 250 * 64 * 8
     assert lib.specvlm_head_argmax_workspace_bytes(8, 60, 32000) == 256 + 8 * 250 * 64 * 8
     assert lib.specvlm_head_argmax_workspace_bytes(0, 60, 32000) == 0

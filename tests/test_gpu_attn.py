@@ -101,6 +101,26 @@ def test_bf16_chain_and_single_node(sv, oracle):
     check(case, *run_both(sv, oracle, case), "single node")
 
 
+def test_vector_alu_measurement_entry_agrees(sv, oracle):
+    """The measurement aid (bf16 input through the vector-ALU kernel, no matrix cores) computes the
+    same operation: within the bf16 tolerance of the oracle, contiguous and paged."""
+    from gpu_util import random_case, i32, to_dev, to_host_f64
+    for paged in (False, True):
+        case = random_case(45, "bf16", B=2, Hq=4, Hkv=2, D=128, N_max=33, P_list=[333, 40], num_nodes=[33, 9], paged=paged)
+        q, k, v = to_dev(case["q"]), to_dev(case["k"]), to_dev(case["v"])
+        out = torch.full_like(q, 7.0)
+        lse = torch.full((2, 4, 33), 7.0, dtype=torch.float32, device="cuda")
+        err = torch.zeros(1, dtype=torch.int32, device="cuda")
+        sv.specvlm_tree_verify_attn_vector_alu(q, k, v, i32(case["prefix_len"]), i32(case["parent"]), out=out, lse=lse,
+                                               num_nodes=i32(case["num_nodes"]), err_flag=err,
+                                               block_table=None if not paged else i32(case["block_table"]))
+        torch.cuda.synchronize()
+        assert int(err.item()) == 0
+        ref_o, ref_lse = oracle.tree_attn(case["q"], case["k"], case["v"], case["prefix_len"], case["parent"],
+                                          case["num_nodes"], block_table=case["block_table"])
+        check(case, to_host_f64(out), to_host_f64(lse), ref_o, ref_lse, f"vector ALU, paged={paged}")
+
+
 def test_bf16_mask_leak_detectors(sv, oracle):
     """V == 1 gives o == 1 up to one bf16 step; huge finite K/V in invisible tree slots and
     NaN beyond the request's end change nothing."""
@@ -156,11 +176,42 @@ def test_error_reporting(sv):
     sv.specvlm_tree_verify_attn(q, k, v, i32([k.shape[2]]), i32(case["parent"]), out=out, err_flag=err)
     torch.cuda.synchronize()
     assert int(err.item()) & 4                                       # prefix + nodes > capacity
+    err.zero_()
+    sv.specvlm_tree_verify_attn(q, k, v, P, i32(case["parent"]), num_nodes=i32([9]), out=out, err_flag=err)
+    torch.cuda.synchronize()
+    assert sv.err_flag_names(int(err.item())) == ["BAD_NUM_NODES"]   # more nodes than N_max
     with pytest.raises(sv.SpecvlmError, match="INVALID_ARG"):
         sv.specvlm_tree_verify_attn(q[..., :96], k[..., :96], v[..., :96], P, i32(case["parent"]))
+    with pytest.raises(sv.SpecvlmError, match="INVALID_ARG"):        # the documented range of num_splits is 0 .. 64
+        sv.specvlm_tree_verify_attn(q, k, v, P, i32(case["parent"]), num_splits=65)
     with pytest.raises(sv.SpecvlmError, match="WORKSPACE_TOO_SMALL"):
         sv.specvlm_tree_verify_attn(q, k, v, P, i32(case["parent"]), num_splits=4,
                                     workspace=torch.zeros(256, dtype=torch.uint8, device="cuda"))
+
+
+@pytest.mark.parametrize("dtype,splits", [("bf16", 1), ("bf16", 3), ("f32", 0)])
+def test_block_table_entry_outside_the_pool_is_reported(sv, oracle, dtype, splits):
+    """A block id outside [0, num_blocks) sets SPECVLM_ERR_BAD_BLOCK (matrix-core and vector-ALU
+    kernels), nothing outside the pool is touched, and the other request's result is unharmed."""
+    from gpu_util import random_case, i32, to_dev, to_host_f64, assert_attn_close
+    case = random_case(75, dtype, B=2, Hq=2, Hkv=2, D=128 if dtype == "bf16" else 64, N_max=20, P_list=[150, 70], paged=True)
+    nb = case["k"].shape[0]
+    ref, _ = oracle.tree_attn(case["q"], case["k"], case["v"], case["prefix_len"], case["parent"],
+                              block_table=case["block_table"])
+    q, k, v = to_dev(case["q"]), to_dev(case["k"]), to_dev(case["v"])
+    P, par = i32(case["prefix_len"]), i32(case["parent"])
+    for bad in (nb, nb + 12345, -1, -(1 << 30)):
+        table = case["block_table"].copy()
+        table[0, 3] = bad                                            # inside request 0's prefix
+        err = torch.zeros(1, dtype=torch.int32, device="cuda")
+        out = sv.specvlm_tree_verify_attn(q, k, v, P, par, block_table=i32(table), err_flag=err, num_splits=splits)
+        torch.cuda.synchronize()
+        assert sv.err_flag_names(int(err.item())) == ["BAD_BLOCK"], bad
+        assert_attn_close(to_host_f64(out)[1], ref[1], dtype, f"request 1 with a bad entry {bad} in request 0's table")
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    sv.specvlm_tree_verify_attn(q, k, v, P, par, block_table=i32(case["block_table"]), err_flag=err, num_splits=splits)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
 
 
 def test_one_workspace_across_shapes_and_graph_replays(sv, oracle):
@@ -206,8 +257,8 @@ def test_one_workspace_across_shapes_and_graph_replays(sv, oracle):
 
 def test_one_workspace_across_head_counts(sv, oracle):
     """Split calls with 4, 64 and 36 (request, head) pairs alternate on one workspace that was
-    zero-filled once: where one call keeps its arrival tickets another must never have stored partial
-    results, and every call leaves the ticket region zero."""
+    zero-filled once: every call must leave the counter region (a fixed 64 KiB at the start, whatever the shape) zero,
+    and no call may keep partial results where another keeps counters."""
     from gpu_util import random_case, i32, to_dev, to_host_f64, assert_attn_close
     cases = [random_case(84, "bf16", B=1, Hq=4, Hkv=2, D=128, N_max=60, P_list=[400]),
              random_case(85, "bf16", B=2, Hq=32, Hkv=8, D=128, N_max=33, P_list=[150, 260]),
@@ -221,7 +272,7 @@ def test_one_workspace_across_head_counts(sv, oracle):
             q, k, v, P, par = dev[ci]
             out = sv.specvlm_tree_verify_attn(q, k, v, P, par, workspace=ws, num_splits=splits)
             assert_attn_close(to_host_f64(out), refs[ci], "bf16", f"round {rnd} case {ci} splits {splits}")
-            assert int(ws[:4096 * 16].view(torch.int32).abs().max()) == 0, "ticket region not left zero"
+            assert int(ws[:4096 * 16].view(torch.int32).abs().max()) == 0, "counter region not left zero"
 
 
 @pytest.mark.parametrize("seed", range(24))

@@ -133,6 +133,42 @@ def test_compact_matches_oracle(sv, oracle, dtype, D, paged, alias):
     assert np.array_equal(to_host_bits(kd), k) and np.array_equal(to_host_bits(vd), v)
 
 
+def test_compact_skips_moves_through_a_bad_block_id(sv, oracle):
+    """Paged cache with block ids outside the pool in one request's table: SPECVLM_ERR_BAD_BLOCK is
+    set, the moves that would touch such a block are not made (nothing is written into a block the
+    table does not validly name), every other move is the oracle's."""
+    from gpu_util import i32, to_dev, to_host_bits
+    rng = np.random.default_rng(7)
+    L, B, H, bs, D = 2, 2, 2, 16, 128
+    P = np.array([10, 29], dtype=np.int32)                       # both requests' paths straddle two blocks
+    paths = np.array([[0, 2, 5, 9], [0, 2, 4, 6]], dtype=np.int32)
+    m = np.array([3, 3], dtype=np.int32)
+    table, nb = W.block_table(rng, B, 3, spare=0.5)
+    k = rng.integers(0, 65536, size=(L, nb, H, bs, D), dtype=np.uint16)
+    v = rng.integers(0, 65536, size=(L, nb, H, bs, D), dtype=np.uint16)
+    for bad in (nb, -3):
+        bad_table = table.copy()
+        bad_table[0, 1] = bad                                    # request 0: slots 16..31 are unreachable
+        kd, vd = to_dev(k), to_dev(v)
+        err = torch.zeros(1, dtype=torch.int32, device="cuda")
+        sv.specvlm_kv_compact(kd, vd, i32(P), i32(paths), i32(m), block_table=i32(bad_table), err_flag=err)
+        torch.cuda.synchronize()
+        assert sv.err_flag_names(int(err.item())) == ["BAD_BLOCK"]
+        # expected: request 1 as the oracle moves it; of request 0 the two moves inside block 0
+        # (slots 11 <- 12, 12 <- 15), not the one whose source, slot 19, lies in the unreachable block
+        ke, ve = k.copy(), v.copy()
+        valid = np.array([[0, 2, 5, -1], paths[1]], dtype=np.int32)
+        oracle.kv_compact(ke, ve, P, valid, np.array([2, 3], dtype=np.int32), block_table=table)
+        assert np.array_equal(to_host_bits(kd), ke) and np.array_equal(to_host_bits(vd), ve)
+    kd, vd = to_dev(k), to_dev(v)
+    err = torch.zeros(1, dtype=torch.int32, device="cuda")
+    sv.specvlm_kv_compact(kd, vd, i32(P), i32(paths), i32(m), block_table=i32(table), err_flag=err)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    oracle.kv_compact(k, v, P, paths, m, block_table=table)
+    assert np.array_equal(to_host_bits(kd), k) and np.array_equal(to_host_bits(vd), v)
+
+
 def test_compact_layer_pointer_array(sv, oracle):
     """Layers allocated separately and passed as a device array of pointers."""
     from gpu_util import i32, to_dev, to_host_bits

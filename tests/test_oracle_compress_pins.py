@@ -1,5 +1,5 @@
-"""Pins of the oracle's parameter-free visual token compressors (SpecVLM Sec. 3.3: pruning drops
-tokens at random, pooling is a vanilla operator; Table 4: ratios 2x to 30x).  Both are plain
+"""Pins of the oracle's parameter-free visual token compressors (SpecVLM Sec. 3.4: the pruning
+expert discards a random subset of the tokens, pooling is a plain operator; Table 4: ratios 2x to 30x).  Both are plain
 definitions; they are pinned against numpy's reshape-mean / fancy indexing and closed forms."""
 import numpy as np
 import pytest
