@@ -45,7 +45,68 @@ def test_hand_worked_fixture(oracle, case):
     assert path[0].tolist() == want_path + [-1] * (4 - len(want_path))
     assert committed[0].tolist() == want_comm + [-1] * (4 - len(want_comm))
     assert bonus[0] == want_comm[-1]
-    assert info["margin_accept"][0] > 5e-3 and info["margin_bonus"][0] > 5e-3   # not on a boundary
+    # the diagnostics that decide which requests a lower-precision evaluation is held to, hand-worked too
+    # (inputs pass through float32: ln p, u)
+    assert abs(info["margin_accept"][0] - fx[case + "_margin_accept"][0]) < 1e-6
+    assert abs(info["margin_bonus"][0] - fx[case + "_margin_bonus"][0]) < 1e-6
+    assert info["bonus_alt"][0] == int(fx[case + "_bonus_alt"][0])
+
+
+def test_margins_against_cumulative_sums(oracle):
+    """margin_accept, margin_bonus and bonus_alt by brute force: a root with a few leaf children over a
+    small vocabulary (some tokens of probability 0, some children repeating a token), thresholds and CDF
+    edges from numpy's cumulative sums in float64."""
+    rng = np.random.default_rng(2509)
+    for trial in range(400):
+        V = int(rng.integers(2, 9))
+        K = int(rng.integers(0, 5))                                   # children of the root, all leaves
+        N = K + 1
+        parent = np.array([[-1] + [0] * K], dtype=np.int32)
+        logits = rng.normal(0.0, 1.5, size=(1, N, V)).astype(np.float32)
+        dead = rng.random(V) < 0.25
+        if dead.all():
+            dead[int(rng.integers(0, V))] = False
+        logits[0, :, dead] = -np.inf
+        tok = np.concatenate([[0], rng.integers(-1, V + 1, size=K)]).astype(np.int32)[None]   # some out of range
+        ua = rng.random((1, N), dtype=np.float32)
+        ub = rng.random(1, dtype=np.float32)
+        T = float(rng.choice([1.0, 0.5, 2.0]))
+        m, path, bonus, committed, info = oracle.tree_accept_sample(parent, tok, logits, ua, ub, temperature=T, path_cap=4)
+
+        def probs(row):
+            z = np.exp((row.astype(np.float64) - row[np.isfinite(row)].max()) / T)
+            return z / z.sum()
+
+        p = probs(logits[0, 0])
+        rejected = np.zeros(V, dtype=bool)
+        margin, cur = 1.0, 0
+        for c in range(1, N):
+            x = int(tok[0, c])
+            if not (0 <= x < V) or rejected[x]:
+                continue                                             # rejected whatever the precision: not a comparison
+            a = p[x] / (1.0 - p[rejected].sum())
+            margin = min(margin, abs(float(ua[0, c]) - a))
+            if float(ua[0, c]) < a:
+                cur = c
+                break
+            rejected[x] = True
+        if cur:                                                      # a leaf: its own distribution, nothing rejected
+            p, rejected = probs(logits[0, cur]), np.zeros(V, dtype=bool)
+        assert m[0] == (1 if cur else 0) and path[0, :2].tolist() == ([0, cur] if cur else [0, -1])
+        assert abs(info["margin_accept"][0] - margin) < 1e-9
+        live = np.nonzero(~rejected & (p > 0))[0]
+        mass = p[live]
+        edges = np.concatenate([[0.0], np.cumsum(mass)])             # token live[i] covers [edges[i], edges[i+1])
+        t = float(ub[0]) * edges[-1]
+        i = min(int(np.searchsorted(edges, t, side="right")) - 1, len(live) - 1)
+        assert bonus[0] == live[i]
+        d_lo, d_hi = (t - edges[i]) / edges[-1], (edges[i + 1] - t) / edges[-1]
+        j = i - 1 if d_lo <= d_hi else i + 1
+        if 0 <= j < len(live):
+            assert info["bonus_alt"][0] == live[j]
+            assert abs(info["margin_bonus"][0] - min(d_lo, d_hi)) < 1e-9
+        else:                                                        # no token across the nearer edge
+            assert info["bonus_alt"][0] == live[i] and info["margin_bonus"][0] == 1.0
 
 
 def _tiny_tree():
