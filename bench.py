@@ -25,17 +25,29 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 
-# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/),
-# keyed by workload; None until measured.
-MEASURED_TRAFFIC = {
-    # profiles/attn_mfma_kernel_C3.txt: 29073.7 FETCH_SIZE units x 2.000 KiB + 4740.0 WRITE_SIZE units x 1.000 KiB
-    "C3": {"read_bytes": 59542937, "write_bytes": 4853760, "bytes": 64396697},
-}
-# the same for the fused output head (profiles/head_argmax_kernel_C3.txt); None until measured
-MEASURED_TRAFFIC_HEAD = {
-    # 130048.2 FETCH_SIZE units x 2.000 KiB + 133.1 WRITE_SIZE units x 1.000 KiB
-    "C3": {"read_bytes": 266338714, "write_bytes": 136294, "bytes": 266475008},
-}
+
+
+def measured_traffic(profile_name: str, source_name: str):
+    """HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
+    profiles/<profile_name>: the summary ends with a `traffic_json:` line that names the commit
+    it was taken at and the SHA-256 of the kernel's source file at that commit.  Returns None when
+    there is no such line or when the kernel source has changed since (the counters then describe
+    another kernel)."""
+    import hashlib
+    try:
+        with open(os.path.join(ROOT, "profiles", profile_name)) as f:
+            lines = [l for l in f if l.startswith("traffic_json:")]
+        rec = json.loads(lines[-1][len("traffic_json:"):])
+        with open(os.path.join(ROOT, "paper_2509_11815_amd", "csrc", source_name), "rb") as f:
+            sha = hashlib.sha256(f.read()).hexdigest()
+    except (OSError, IndexError, ValueError):
+        return None
+    if rec.get("source_sha256") != sha:
+        return None
+    return {"read_bytes": rec["read_bytes"], "write_bytes": rec["write_bytes"],
+            "bytes": rec["read_bytes"] + rec["write_bytes"], "taken_at_commit": rec.get("commit"),
+            "from": "profiles/" + profile_name}
+
 
 
 def parse_args():
@@ -48,8 +60,13 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--skip-cpu", action="store_true", help="skip the CPU oracle baseline leg")
     ap.add_argument("--evidence", action="store_true",
-                    help="also time all layers folded into one batched attention call (evidence only; off by default so "
-                         "that a kernel trace of the default run holds per-layer calls only)")
+                    help="also time all layers folded into one batched attention call, and one layer through the "
+                         "vector-ALU kernel (evidence only; off by default so that a kernel trace of the default run "
+                         "holds per-layer matrix-core calls only)")
+    ap.add_argument("--skip-configs", action="store_true",
+                    help="skip the attention-only timings of the other bf16 configurations (C2, C4, C5)")
+    ap.add_argument("--vector-alu", action="store_true",
+                    help="profile helper: with --attn-only, run the layers through specvlm_tree_verify_attn_vector_alu")
     ap.add_argument("--skip-ceilings", action="store_true", help="skip the library copy / read-only bandwidth legs")
     ap.add_argument("--attn-only", action="store_true", help="profile helper: run only the attention launches")
     ap.add_argument("--pool-only", action="store_true",
@@ -134,7 +151,7 @@ def main():
         # per-node argmax and the greedy acceptance walk as one launch, compaction as one more
         sv.specvlm_node_argmax_accept(logits, parent, draft_tok, counters=counters, amax=amax, err_flag=err, out=acc_out)
         # the prefix length is NOT advanced between steps, so every step sees the same workload
-        sv.specvlm_kv_compact(k, v, prefix_len, acc_out[1], acc_out[0], block_table=table, new_prefix_len=new_prefix)
+        sv.specvlm_kv_compact(k, v, prefix_len, acc_out[1], acc_out[0], block_table=table, new_prefix_len=new_prefix, err_flag=err)
 
     def step():
         attn_layers()
@@ -154,17 +171,27 @@ def main():
             fn()
         return g.replay
 
-    def timed(run, iters, warmup):
+    def timed(run, iters, warmup, stats=None):
+        """ms per iteration: `iters` iterations timed as up to 5 equal back-to-back batches between HIP
+        events recorded on the stream the library calls are launched on (torch's current stream, which
+        the binding passes to every call); the median batch is returned, the mean goes to `stats`."""
         for _ in range(warmup):
             run()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(iters):
-            run()
-        e1.record()
+        nb = min(5, iters)
+        sizes = [iters // nb + (1 if i < iters % nb else 0) for i in range(nb)]
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(nb + 1)]
+        ev[0].record()
+        for i, n in enumerate(sizes):
+            for _ in range(n):
+                run()
+            ev[i + 1].record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters          # ms per iteration
+        per = sorted(ev[i].elapsed_time(ev[i + 1]) / sizes[i] for i in range(nb))
+        if stats is not None:
+            stats["mean"] = ev[0].elapsed_time(ev[nb]) / iters
+            stats["min"], stats["max"] = per[0], per[-1]
+        return per[nb // 2]
 
     if args.head_only:
         E_h = 128 * H
@@ -197,6 +224,15 @@ def main():
         print(json.dumps({"visual_pool_ms_per_call": ms, "bytes_per_call": nbytes,
                           "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_of_8TBps": round(nbytes / (ms * 1e-3) / 8e12, 4)}))
         return
+    if args.attn_only and args.vector_alu:
+        # measurement aid: the same layers through the vector-ALU kernel (no matrix cores); slow, so few layers
+        def valu_layers():
+            for l in range(min(L, 4)):
+                sv.specvlm_tree_verify_attn_vector_alu(q[l], k[l], v[l], prefix_len, parent, block_table=table,
+                                                       out=out[l], err_flag=err, desc=desc)
+        ms = timed(make_runner(valu_layers), args.steps, args.warmup)
+        print(json.dumps({"vector_alu_ms_per_layer_call": ms / min(L, 4)}))
+        return
     if args.attn_only:
         run_attn = make_runner(attn_layers)
         ms = timed(run_attn, args.steps, args.warmup)
@@ -204,9 +240,10 @@ def main():
         return
 
     run_step = make_runner(step)
-    ms_step = timed(run_step, args.steps, args.warmup)
+    step_stats = {}
+    ms_step = timed(run_step, args.steps, args.warmup, step_stats)
     run_attn = make_runner(attn_layers)
-    ms_attn = timed(run_attn, args.steps, args.warmup)
+    ms_attn = timed(run_attn, max(args.steps, 100), max(args.warmup, 10))
     # Evidence only, never the headline: the same L x B layer problems handed over as ONE call (layers
     # folded into the batch dimension).  A model cannot do this -- a layer's queries depend on the layer
     # before -- but it shows what the kernel streams once the per-call fixed costs (launch, first-tile
@@ -220,6 +257,56 @@ def main():
         run_fold = make_runner(lambda: sv.specvlm_tree_verify_attn(qf, kf, vf, pf, parf, out=of, workspace=wsf,
                                                                    err_flag=err, desc=dfold))
         ms_folded = timed(run_fold, max(args.steps // 4, 5), 3)
+    # Evidence as well: one layer through the vector-ALU kernel (the measurement aid of the header), i.e. what
+    # the step costs without the matrix cores.
+    ms_valu = None
+    if args.evidence:
+        ms_valu = timed(make_runner(lambda: sv.specvlm_tree_verify_attn_vector_alu(
+            q[0], k[0], v[0], prefix_len, parent, block_table=table, out=out[0], err_flag=err, desc=desc)), 5, 2)
+
+    # ---- the other bf16 configurations, attention only, same method (HIP-graph replay of per-layer calls,
+    # every layer its own K/V memory; at most 8 layers are built -- 1.1 to 3.2 GB, far beyond the 256 MB cache)
+    def attention_only(name):
+        c = W.CONFIGS[name]
+        Lc = min(c.L, 8)
+        Pc = W.prefix_lengths(c)
+        Sc = Pc.astype(np.int64) + c.N
+        qc = torch.randn((Lc, c.B, c.N, c.H, c.D), dtype=torch.bfloat16, device=dev)
+        if c.paged:
+            bpr = W.round_up(int(Sc.max()), c.block_size) // c.block_size
+            t_np, nbc = W.block_table(np.random.default_rng(W.config_seed(c, 0, 3)), c.B, bpr)
+            shape, tbl = (Lc, nbc, c.H, c.block_size, c.D), torch.from_numpy(t_np).to(dev)
+        else:
+            shape, tbl = (Lc, c.B, c.H, W.round_up(int(Sc.max()), 16), c.D), None
+        kc = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+        vc = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+        for l in range(Lc):
+            kc[l].normal_()
+            vc[l].normal_()
+        par_c = torch.from_numpy(W.make_trees(c).parent).to(dev)
+        P_dev = torch.from_numpy(Pc).to(dev)
+        oc = torch.empty_like(qc)
+        dc = sv.binding.make_attn_desc(qc[0], kc[0], oc[0], block_table=tbl)
+        wsc = torch.zeros(max(sv.specvlm_tree_verify_attn_workspace_bytes(dc), 256), dtype=torch.uint8, device=dev)
+
+        def layers():
+            for l in range(Lc):
+                sv.specvlm_tree_verify_attn(qc[l], kc[l], vc[l], P_dev, par_c, block_table=tbl, out=oc[l],
+                                            workspace=wsc, err_flag=err, desc=dc)
+
+        us = timed(make_runner(layers), 40, 10) * 1e3 / Lc
+        nbytes = W.kv_bytes_per_layer(c)
+        return {"attn_us_per_launch": round(us, 3), "algorithmic_bytes_per_launch": nbytes,
+                "GBps": round(nbytes / (us * 1e-6) / 1e9, 1), "frac": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                "num_splits": sv.specvlm_tree_verify_attn_num_splits(dc), "layers_timed": Lc,
+                "shape": f"B={c.B}, H={c.H}, D={c.D}, prefix={Pc.tolist()}, paged={c.paged}"}
+
+    other_configs = {}
+    if not args.skip_configs:
+        for name in ("C2", "C4", "C5"):
+            if name != cfg.name:
+                other_configs[name] = attention_only(name)
+                torch.cuda.empty_cache()
     run_tail = make_runner(sample_and_compact)
     ms_tail = timed(run_tail, args.steps, args.warmup)
     # not part of the step (the headline metric is greedy): the temperature-1 acceptance walk on the same trees
@@ -300,6 +387,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_step, 5),
+        "ms_per_step_note": "median of up to 5 equal batches of the timed steps; mean %.5f, fastest batch %.5f, slowest %.5f"
+                            % (step_stats["mean"], step_stats["min"], step_stats["max"]),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -308,6 +397,7 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.note}; B={B}, L={L}, H={H}, D={D}, prefix={P.tolist()}, "
                                f"tree nodes={N}, depth={cfg.depth}, vocab={cfg.V}, paged={cfg.paged}",
                    "launch": "HIP graph replay of one whole step" if not args.no_graph else "eager launches",
+                   "timing": "HIP events on the stream the calls are launched on",
                    "num_splits": sv.specvlm_tree_verify_attn_num_splits(desc),
                    "accept_len": acc_out[0].tolist()},
         "verify_steps_per_s": round(1e3 / ms_step, 1),
@@ -318,19 +408,26 @@ def main():
             "frac_of_peak": round(kv_bytes_step / (ms_folded * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
             "note": "all layers' attention as one call with batch L*B: not possible in a model (layers depend on "
                     "each other), shows the streaming rate without L-fold per-call costs"},
+        "evidence_vector_alu_kernel": None if ms_valu is None else {
+            "us_per_layer_call": round(ms_valu * 1e3, 1), "GBps": round(W.kv_bytes_per_layer(cfg) / (ms_valu * 1e-3) / 1e9, 1),
+            "note": "one layer through specvlm_tree_verify_attn_vector_alu (no matrix cores): what the matrix-core kernel is measured against"},
         "outside_the_step_ms": {"tree_accept_sample_T1": round(ms_smp, 5), "draft_tree_growth": round(ms_grow, 5),
                                 "head_argmax_fused": round(ms_head, 5)},
         "roofline_head_argmax": {"kernel": "specvlm::head_argmax_kernel<%d>" % (1 if B * N <= 64 else 2 if B * N <= 128 else 4 if B * N <= 256 else 8), "bound": "hbm",
                                  "achieved": round(head_bytes / (ms_head * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
                                  "unit": "GB/s", "frac": round(head_bytes / (ms_head * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                                  "algorithmic_bytes_per_launch": head_bytes, "avg_launch_us": round(ms_head * 1e3, 3),
-                                 "traffic": MEASURED_TRAFFIC_HEAD.get(cfg.name)},
+                                 "traffic": measured_traffic("head_argmax_kernel_C3.txt", "head_argmax.hip") if cfg.name == "C3" else None},
         "roofline": {"kernel": "specvlm::attn_mfma_kernel<128, 4, 2> (the whole specvlm_tree_verify_attn call of one layer)",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": kv_bytes_layer,
                      "avg_launch_us": round(attn_launch_us, 3),
-                     "traffic": MEASURED_TRAFFIC.get(cfg.name)},
+                     "traffic": measured_traffic("attn_mfma_kernel_C3.txt", "attn_mfma.hip") if cfg.name == "C3" else None},
+        "configs": dict({cfg.name: {"attn_us_per_launch": round(attn_launch_us, 3), "algorithmic_bytes_per_launch": kv_bytes_layer,
+                                    "GBps": round(achieved, 1), "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                                    "num_splits": sv.specvlm_tree_verify_attn_num_splits(desc), "layers_timed": L}},
+                        **other_configs),
     }
 
     # ---- what plain library kernels reach on this machine: device copy (read + write) and a read-only pass ----
