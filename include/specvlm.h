@@ -86,7 +86,7 @@ typedef struct specvlm_attn_desc {
     int32_t kv_capacity;           /* slots per request (contiguous); paged: max_blocks_per_req*16 */
     int32_t num_splits;            /* key-range splits per (request, head): 0 lets the library choose, 1 ..
                                       SPECVLM_MAX_SPLITS is taken as given (anything else: SPECVLM_INVALID_ARG);
-                                      with more than 4096 (request, head) pairs a call always runs unsplit */
+                                      with more than 1024 (request, head) pairs a call always runs unsplit */
     int64_t q_stride_b, q_stride_n, q_stride_h;
     int64_t o_stride_b, o_stride_n, o_stride_h;
     int64_t kv_stride_b, kv_stride_h, kv_stride_t;

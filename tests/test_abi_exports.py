@@ -91,7 +91,7 @@ def test_split_choice_and_workspace_sizes_for_the_five_workloads():
         need = lib.specvlm_tree_verify_attn_workspace_bytes(ctypes.byref(d))
         if d.dtype == 0 and want > 1:
             parts = d.B * d.H_q * want
-            counters = 4096 * 4 * 4                                              # a fixed region, whatever the shape
+            counters = 1024 * 4 * 128                                            # a fixed region, whatever the shape: a 128-byte line per counter
             assert need == counters + parts * (64 * d.D * 2 + 64 * 8), name     # bf16 partials + (max, sum) pairs
     d = cases["C3"][0]
     d.num_splits = 5                                                             # a caller's choice is kept
@@ -102,7 +102,7 @@ def test_split_choice_and_workspace_sizes_for_the_five_workloads():
         d.num_splits = bad
         assert lib.specvlm_tree_verify_attn_num_splits(ctypes.byref(d)) == 0
         assert lib.specvlm_tree_verify_attn_workspace_bytes(ctypes.byref(d)) == 0
-    d.num_splits, d.B, d.H_q, d.H_kv = 8, 33, 128, 128                           # 4224 (request, head) pairs: unsplit
+    d.num_splits, d.B, d.H_q, d.H_kv = 8, 9, 128, 128                            # 1152 (request, head) pairs: unsplit
     assert lib.specvlm_tree_verify_attn_num_splits(ctypes.byref(d)) == 1
     d.num_splits, d.B, d.H_q, d.H_kv = 0, 1, 32, 32
     assert lib.specvlm_head_argmax_workspace_bytes(1, 60, 32000) == 256 + 250 * 64 * 8

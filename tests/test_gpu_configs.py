@@ -56,8 +56,8 @@ def test_attention_full_size(sv, oracle, name, layers, heads):
                                           block_table=lay.block_table)
         assert_attn_close(to_host_f64(out), ref_o, cfg.dtype, f"{name} layer {layer}")
         assert np.abs(to_host_f64(lse) - ref_lse).max() <= 2e-2
-    ncnt = cfg.B * q.shape[2] * 4                                      # one int32 ticket per (request, head)
-    assert int(workspace[:ncnt].to(torch.int32).sum().item()) == 0     # counters left at zero
+    ncnt = min(1024 * 4 * 128, workspace.numel())                      # the ticket counters' fixed region
+    assert int(workspace[:ncnt].view(torch.int32).abs().max().item()) == 0     # counters left at zero
 
 
 def _rand_bits(rng, shape):
