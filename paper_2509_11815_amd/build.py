@@ -33,6 +33,34 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def kernel_resource_usage(source: str) -> dict:
+    """Per-kernel VGPR count, scratch bytes per lane and LDS bytes of one source file, from the
+    compiler's own kernel-resource-usage remarks (device code only, nothing is linked)."""
+    import re
+    import tempfile
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    with tempfile.TemporaryDirectory() as tmp:
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, "-I" + CSRC,
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form",
+               "-Rpass-analysis=kernel-resource-usage", "--cuda-device-only", "-c", "-o", os.path.join(tmp, "k.o"),
+               os.path.join(CSRC, source)]
+        proc = subprocess.run(cmd, capture_output=True, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + proc.stderr)
+    out, name = {}, None
+    for line in proc.stderr.splitlines():
+        m = re.search(r"remark: Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+            out[name] = {}
+        for key, pat in (("vgprs", r"\bVGPRs: (\d+)"), ("scratch", r"ScratchSize \[bytes/lane\]: (\d+)"),
+                         ("lds", r"LDS Size \[bytes/block\]: (\d+)")):
+            m = re.search(pat, line)
+            if m and name:
+                out[name][key] = int(m.group(1))
+    return out
+
+
 def needs_build() -> bool:
     if not os.path.exists(LIB):
         return True

@@ -108,3 +108,21 @@ def test_split_choice_and_workspace_sizes_for_the_five_workloads():
     assert lib.specvlm_head_argmax_workspace_bytes(1, 60, 32000) == 256 + 250 * 64 * 8
     assert lib.specvlm_head_argmax_workspace_bytes(8, 60, 32000) == 256 + 8 * 250 * 64 * 8
     assert lib.specvlm_head_argmax_workspace_bytes(0, 60, 32000) == 0
+
+
+def test_attention_kernels_spill_nothing():
+    """The matrix-core attention kernels count their outstanding memory operations by hand
+    (s_waitcnt vmcnt) and read results of hand-written loads after hand-written waits: a register
+    spilled to scratch memory would add memory operations the count does not know, and could save a
+    register before its load has landed.  So they must compile without scratch, and the shape
+    meant for two workgroups per compute unit must stay within 128 registers and half the LDS."""
+    from paper_2509_11815_amd import build
+    usage = build.kernel_resource_usage("attn_mfma.hip")
+    kernels = {k: v for k, v in usage.items() if "attn_mfma_kernel" in k}
+    assert len(kernels) == 4, sorted(usage)                    # two shapes x two head sizes
+    for name, u in kernels.items():
+        assert u["scratch"] == 0, (name, u)
+        if "2wg" in name:
+            assert u["vgprs"] <= 128 and u["lds"] <= 80 * 1024, (name, u)
+        else:
+            assert u["lds"] <= 160 * 1024, (name, u)
