@@ -27,19 +27,27 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 
 
 
-def measured_traffic(profile_name: str, source_name: str):
+def source_sha256(*source_names: str) -> str:
+    """SHA-256 over the named kernel source files under csrc/, in the order given."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in source_names:
+        with open(os.path.join(ROOT, "paper_2509_11815_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(profile_name: str, *source_names: str):
     """HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
     profiles/<profile_name>: the summary ends with a `traffic_json:` line that names the commit
-    it was taken at and the SHA-256 of the kernel's source file at that commit.  Returns None when
+    it was taken at and the SHA-256 of the kernel's source files at that commit.  Returns None when
     there is no such line or when the kernel source has changed since (the counters then describe
     another kernel)."""
-    import hashlib
     try:
         with open(os.path.join(ROOT, "profiles", profile_name)) as f:
             lines = [l for l in f if l.startswith("traffic_json:")]
         rec = json.loads(lines[-1][len("traffic_json:"):])
-        with open(os.path.join(ROOT, "paper_2509_11815_amd", "csrc", source_name), "rb") as f:
-            sha = hashlib.sha256(f.read()).hexdigest()
+        sha = source_sha256(*source_names)
     except (OSError, IndexError, ValueError):
         return None
     if rec.get("source_sha256") != sha:
@@ -423,7 +431,7 @@ def main():
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": kv_bytes_layer,
                      "avg_launch_us": round(attn_launch_us, 3),
-                     "traffic": measured_traffic("attn_mfma_kernel_C3.txt", "attn_mfma.hip") if cfg.name == "C3" else None},
+                     "traffic": measured_traffic("attn_mfma_kernel_C3.txt", "attn_mfma.hip", "attn_mfma_body.inc") if cfg.name == "C3" else None},
         "configs": dict({cfg.name: {"attn_us_per_launch": round(attn_launch_us, 3), "algorithmic_bytes_per_launch": kv_bytes_layer,
                                     "GBps": round(achieved, 1), "frac": round(achieved / HBM_PEAK_GBPS, 4),
                                     "num_splits": sv.specvlm_tree_verify_attn_num_splits(desc), "layers_timed": L}},
