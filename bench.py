@@ -274,7 +274,10 @@ def main():
 
     # ---- the other bf16 configurations, attention only, same method (HIP-graph replay of per-layer calls,
     # every layer its own K/V memory; at most 8 layers are built -- 1.1 to 3.2 GB, far beyond the 256 MB cache)
-    def attention_only(name):
+    def attention_only(name, capacity=None, tail=False):
+        """One attention call per layer of configuration `name` (up to 8 layers resident), graph replay.
+        `capacity` (contiguous caches): a cache preallocated for that many slots instead of one that
+        just fits the lengths.  `tail`: also time the configuration's argmax + accept launch."""
         c = W.CONFIGS[name]
         Lc = min(c.L, 8)
         Pc = W.prefix_lengths(c)
@@ -285,7 +288,7 @@ def main():
             t_np, nbc = W.block_table(np.random.default_rng(W.config_seed(c, 0, 3)), c.B, bpr)
             shape, tbl = (Lc, nbc, c.H, c.block_size, c.D), torch.from_numpy(t_np).to(dev)
         else:
-            shape, tbl = (Lc, c.B, c.H, W.round_up(int(Sc.max()), 16), c.D), None
+            shape, tbl = (Lc, c.B, c.H, capacity or W.round_up(int(Sc.max()), 16), c.D), None
         kc = torch.empty(shape, dtype=torch.bfloat16, device=dev)
         vc = torch.empty(shape, dtype=torch.bfloat16, device=dev)
         for l in range(Lc):
@@ -304,17 +307,39 @@ def main():
 
         us = timed(make_runner(layers), 40, 10) * 1e3 / Lc
         nbytes = W.kv_bytes_per_layer(c)
-        return {"attn_us_per_launch": round(us, 3), "algorithmic_bytes_per_launch": nbytes,
-                "GBps": round(nbytes / (us * 1e-6) / 1e9, 1), "frac": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
-                "num_splits": sv.specvlm_tree_verify_attn_num_splits(dc), "layers_timed": Lc,
-                "shape": f"B={c.B}, H={c.H}, D={c.D}, prefix={Pc.tolist()}, paged={c.paged}"}
+        rec = {"attn_us_per_launch": round(us, 3), "algorithmic_bytes_per_launch": nbytes,
+               "GBps": round(nbytes / (us * 1e-6) / 1e9, 1), "frac": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+               "num_splits": sv.specvlm_tree_verify_attn_num_splits(dc), "layers_timed": Lc,
+               "shape": f"B={c.B}, H={c.H}, D={c.D}, prefix={Pc.tolist()}, paged={c.paged}"
+                        + (f", cache capacity {capacity}" if capacity else "")}
+        if tail:
+            # the per-node argmax over the vocabulary + the greedy walk, one launch: B*N*V logits read once
+            tbc = W.make_trees(c)
+            lg = torch.from_numpy(tbc.logits.view(np.int16)).to(dev).view(torch.bfloat16)
+            tok = torch.from_numpy(tbc.draft_tok).to(dev)
+            cnt = torch.zeros(c.B, dtype=torch.int32, device=dev)
+            am = torch.empty((c.B, c.N), dtype=torch.int32, device=dev)
+            oo = (torch.empty(c.B, dtype=torch.int32, device=dev), torch.empty((c.B, c.depth + 1), dtype=torch.int32, device=dev),
+                  torch.empty(c.B, dtype=torch.int32, device=dev), torch.empty((c.B, c.depth + 1), dtype=torch.int32, device=dev))
+            us_t = timed(make_runner(lambda: sv.specvlm_node_argmax_accept(lg, par_c, tok, counters=cnt, amax=am,
+                                                                           err_flag=err, out=oo)), 100, 10) * 1e3
+            lbytes = lg.numel() * lg.element_size()
+            rec["node_argmax_accept"] = {"us_per_launch": round(us_t, 3), "algorithmic_bytes_per_launch": lbytes, "bound": "hbm",
+                                         "GBps": round(lbytes / (us_t * 1e-6) / 1e9, 1),
+                                         "frac": round(lbytes / (us_t * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
+        return rec
 
     other_configs = {}
     if not args.skip_configs:
         for name in ("C2", "C4", "C5"):
             if name != cfg.name:
-                other_configs[name] = attention_only(name)
+                other_configs[name] = attention_only(name, tail=(name == "C4"))
                 torch.cuda.empty_cache()
+        # a short request in a cache preallocated for a long one: the split count follows the capacity
+        c3 = W.CONFIGS["C3"]
+        other_configs["C2_lengths_in_a_cache_of_C3_capacity"] = attention_only(
+            "C2", capacity=W.round_up(int(W.prefix_lengths(c3).max()) + c3.N, 16))
+        torch.cuda.empty_cache()
     run_tail = make_runner(sample_and_compact)
     ms_tail = timed(run_tail, args.steps, args.warmup)
     # not part of the step (the headline metric is greedy): the temperature-1 acceptance walk on the same trees
