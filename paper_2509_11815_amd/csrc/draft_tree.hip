@@ -148,10 +148,99 @@ __device__ __forceinline__ int pos_of(const unsigned long long* s_key, int i) {
     return reinterpret_cast<const int*>(s_key)[2 * i];
 }
 
+// Many candidates, few winners (the whole tree's 500 candidates, 59 nodes): ranking everybody
+// against everybody is mostly wasted on candidates that cannot win.  The candidates are dealt
+// into kGroupsDT groups (candidate i -> group i mod kGroupsDT); the M-th largest of the group
+// maxima is a key that at least M candidates reach, so nobody below it wins, and at most
+// M * ceil(c / kGroupsDT) candidates reach it (the members of M groups).  Only those are ranked,
+// among themselves.  Same result as rank_winners' full ranking: keys are distinct, so "the M
+// greatest keys" is one set whatever way it is found.  Needs kGroupsDT <= c <= kThreadsDT (every
+// group has a member, one candidate per thread) and M <= kGroupsDT.
+constexpr int kGroupsDT = 128;
+
+__device__ __forceinline__ void rank_winners_prefiltered(unsigned long long* s_key, int c, int M) {
+    __shared__ unsigned long long s_gmax[kGroupsDT];
+    __shared__ unsigned long long s_surv[kThreadsDT];
+    __shared__ unsigned long long s_thr;
+    __shared__ int s_cnt2[kThreadsDT];
+    __shared__ int s_wcount2[kWavesDT];
+    __shared__ uint32_t s_winmask[kThreadsDT / 32];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const unsigned long long ki = tid < c ? s_key[tid] : 0ull;          // 0: below every real key
+    if (tid < kGroupsDT) {
+        unsigned long long m = ki;
+        for (int i = tid + kGroupsDT; i < c; i += kGroupsDT) {
+            const unsigned long long k = s_key[i];
+            m = k > m ? k : m;
+        }
+        s_gmax[tid] = m;
+    }
+    s_cnt2[tid] = 0;
+    if (tid < kThreadsDT / 32) s_winmask[tid] = 0u;
+    __syncthreads();
+    // rank of every group maximum among the group maxima: four threads per maximum, a quarter each
+    {
+        const int j = tid & (kGroupsDT - 1), part = tid / kGroupsDT;
+        constexpr int kPer = kGroupsDT / (kThreadsDT / kGroupsDT);
+        const unsigned long long kj = s_gmax[j];
+        int beaten = 0;
+#pragma unroll 8
+        for (int x = part * kPer; x < (part + 1) * kPer; ++x) beaten += s_gmax[x] > kj ? 1 : 0;
+        atomicAdd(&s_cnt2[j], beaten);
+    }
+    __syncthreads();
+    if (tid < kGroupsDT && s_cnt2[tid] == M - 1) s_thr = s_gmax[tid];    // exactly one thread: the ranks are a permutation
+    __syncthreads();
+    const unsigned long long thr = s_thr;
+    // the candidates that reach the threshold, gathered in index order
+    const bool surv = ki >= thr;                                         // thr is a real key: never true for tid >= c
+    const unsigned long long bal = __ballot(surv);
+    if (lane == 0) s_wcount2[wave] = __popcll(bal);
+    s_cnt2[tid] = 0;
+    __syncthreads();
+    int before = 0, ns = 0;
+#pragma unroll
+    for (int x = 0; x < kWavesDT; ++x) {
+        const int n = s_wcount2[x];
+        before += x < wave ? n : 0;
+        ns += n;
+    }
+    if (surv) s_surv[before + __popcll(bal & ((1ull << lane) - 1ull))] = ki;
+    if (tid < c) reinterpret_cast<int*>(s_key)[2 * tid] = -1;           // every key is in a register or in s_surv by now
+    __syncthreads();
+    // rank among the ns survivors: `parts` threads per survivor, a slice each
+    int nsp = 64;                                                        // uniform: survivors rounded up to a power of two
+    while (nsp < ns) nsp *= 2;
+    const int parts = kThreadsDT / nsp, per = (ns + parts - 1) / parts;
+    const int a = tid & (nsp - 1), part = tid / nsp;
+    const unsigned long long ka = a < ns ? s_surv[a] : ~0ull;
+    {
+        int beaten = 0;
+        const int x1 = min(ns, (part + 1) * per);
+        for (int x = part * per; x < x1; ++x) beaten += s_surv[x] > ka ? 1 : 0;
+        if (a < ns) atomicAdd(&s_cnt2[a], beaten);
+    }
+    __syncthreads();
+    const bool win = part == 0 && a < ns && s_cnt2[a] < M;
+    const uint32_t idx = 0xFFFFFFFFu - static_cast<uint32_t>(ka);       // the candidate's index sits in the key's low word
+    if (win) atomicOr(&s_winmask[idx >> 5], 1u << (idx & 31));
+    __syncthreads();
+    if (win) {                                                           // position = winners of lower index
+        int pos = __popc(s_winmask[idx >> 5] & ((1u << (idx & 31)) - 1u));
+        for (uint32_t w = 0; w < (idx >> 5); ++w) pos += __popc(s_winmask[w]);
+        reinterpret_cast<int*>(s_key)[2 * idx] = pos;
+    }
+    __syncthreads();
+}
+
 __device__ __forceinline__ void rank_winners(unsigned long long* s_key, int c, int M) {
     __shared__ int s_wcount[kWavesDT];
     __shared__ int s_cnt[kThreadsDT];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (c >= 2 * kGroupsDT && c <= kThreadsDT && M >= 1 && M <= kGroupsDT / 2) {    // uniform
+        rank_winners_prefiltered(s_key, c, M);
+        return;
+    }
     // `parts` groups of wavefronts share the candidates of a pass: group `part` counts, for every
     // candidate of the pass, the keys of its slice [j0, j1) of the others that beat it.
     int parts = 1, shift = 0;                              // uniform; a group is at least one wavefront

@@ -97,7 +97,8 @@ def test_topk_when_the_best_tokens_are_neighbours(sv, oracle, dtype, V, K):
     assert r_token[2].tolist() == list(range(K))                          # all equal: the lowest tokens
 
 
-@pytest.mark.parametrize("C,M", [(1, 1), (10, 10), (100, 10), (610, 59), (1500, 64), (8192, 40)])
+@pytest.mark.parametrize("C,M", [(1, 1), (10, 10), (100, 10), (610, 59), (1500, 64), (8192, 40), (256, 64), (1024, 64),
+                                 (1023, 1), (700, 33), (1024, 65)])
 def test_select_matches_oracle(sv, oracle, C, M):
     from gpu_util import i32
     rng = np.random.default_rng(C + M)
@@ -120,6 +121,26 @@ def test_select_matches_oracle(sv, oracle, C, M):
     sel2, _, _ = sv.specvlm_draft_select(wide[:, 7:], M)
     r2, _, _ = oracle.tree_select(score, M)
     assert np.array_equal(sel2.cpu().numpy(), r2)
+
+
+@pytest.mark.parametrize("C,M", [(1024, 64), (510, 59), (777, 20)])
+def test_select_when_the_winners_crowd_together(sv, oracle, C, M):
+    """Score patterns that are hard on a selection which first discards by a threshold: all scores equal
+    (the index decides everything), sorted either way, and every high score in candidates i with
+    i mod 128 < M (whole residue classes high, so a threshold from class maxima discards the least)."""
+    i = np.arange(C)
+    rng = np.random.default_rng(C * 7 + M)
+    rows = [np.zeros(C), -i.astype(np.float64), i.astype(np.float64), np.where(i % 128 < M, 5.0, -5.0),
+            np.where(i % 128 < M, 5.0 + (i // 128), -5.0), np.where(i % 128 < M, rng.normal(5, 1, C), rng.normal(-5, 1, C)),
+            np.where(i % 128 == 3, 1.0, 0.0), np.full(C, -np.inf)]
+    score = np.stack(rows).astype(np.float32)
+    sel, sel_score, count = sv.specvlm_draft_select(_f32(score), M)
+    r_sel, r_count, _ = oracle.tree_select(score, M)
+    assert np.array_equal(sel.cpu().numpy(), r_sel)
+    assert np.array_equal(count.cpu().numpy(), r_count)
+    got_sc = sel_score.cpu().numpy()
+    for b in range(len(rows)):
+        assert np.array_equal(got_sc[b, :r_count[b]], score[b, r_sel[b, :r_count[b]]])
 
 
 @pytest.mark.parametrize("dtype,V", [("bf16", 32000), ("f32", 1000), ("bf16", 40000), ("bf16", 70001)])
