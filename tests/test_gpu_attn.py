@@ -78,6 +78,18 @@ def test_bf16_split_counts_span_tiles_and_tail(sv, oracle, num_splits):
     check(case, *run_both(sv, oracle, case, num_splits=num_splits), f"splits={num_splits}")
 
 
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("D,num_splits", [(128, 4), (64, 6), (128, 6)])
+def test_bf16_between_one_and_two_workgroups_per_compute_unit(sv, oracle, D, num_splits, paged):
+    """80 (request, head) pairs x 4 or 6 splits = 320 or 480 work items: more than the chip's 256 compute
+    units, at most two per unit -- the launch shape with the small rings.  Ragged lengths, an empty
+    prefix, grouped KV heads, more splits than the short requests have tiles."""
+    from gpu_util import random_case
+    case = random_case(51 + D + num_splits, "bf16", B=5, Hq=16, Hkv=8, D=D, N_max=37,
+                       P_list=[300, 0, 77, 150, 513], num_nodes=[37, 5, 20, 1, 33], paged=paged)
+    check(case, *run_both(sv, oracle, case, num_splits=num_splits), f"2 per CU D={D} splits={num_splits} paged={paged}")
+
+
 @pytest.mark.parametrize("D", [64, 128])
 def test_bf16_paged_cache(sv, oracle, D):
     from gpu_util import random_case
