@@ -153,7 +153,7 @@ def main():
             sv.specvlm_tree_verify_attn(q[l], k[l], v[l], prefix_len, parent, block_table=table, out=out[l],
                                         workspace=workspace, err_flag=err, desc=desc)
 
-    counters = torch.zeros(B, dtype=torch.int32, device=dev)
+    counters = torch.zeros(B * sv.binding.COUNTER_STRIDE, dtype=torch.int32, device=dev)
 
     def sample_and_compact():
         # per-node argmax and the greedy acceptance walk as one launch, compaction as one more
@@ -317,7 +317,7 @@ def main():
             tbc = W.make_trees(c)
             lg = torch.from_numpy(tbc.logits.view(np.int16)).to(dev).view(torch.bfloat16)
             tok = torch.from_numpy(tbc.draft_tok).to(dev)
-            cnt = torch.zeros(c.B, dtype=torch.int32, device=dev)
+            cnt = torch.zeros(c.B * sv.binding.COUNTER_STRIDE, dtype=torch.int32, device=dev)
             am = torch.empty((c.B, c.N), dtype=torch.int32, device=dev)
             oo = (torch.empty(c.B, dtype=torch.int32, device=dev), torch.empty((c.B, c.depth + 1), dtype=torch.int32, device=dev),
                   torch.empty(c.B, dtype=torch.int32, device=dev), torch.empty((c.B, c.depth + 1), dtype=torch.int32, device=dev))
@@ -366,7 +366,7 @@ def main():
            torch.empty((B, N), dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev))
     root_tok = torch.zeros(B, dtype=torch.int32, device=dev)
 
-    grow_counters = torch.zeros(B, dtype=torch.int32, device=dev)
+    grow_counters = torch.zeros(B * sv.binding.COUNTER_STRIDE, dtype=torch.int32, device=dev)
 
     def grow():
         # a level = Top-K of the expanded nodes' rows + the choice of the nodes the next level expands, one launch

@@ -57,6 +57,7 @@ typedef enum specvlm_dtype {
 #define SPECVLM_MAX_NODES 64
 #define SPECVLM_PAGE_SIZE 16
 #define SPECVLM_MAX_SPLITS 64        /* key-range splits per (request, head) */
+#define SPECVLM_COUNTER_STRIDE 32              /* int32 words between the arrival counters of two requests */
 #define SPECVLM_MAX_CANDIDATES 8192  /* draft growth: scored candidates per request */
 
 /*
@@ -223,8 +224,11 @@ int32_t specvlm_tree_accept(int32_t B, int32_t N_max, int32_t path_cap,
  * (request, node) row is reduced as in specvlm_node_argmax, and the workgroup that finishes the
  * last row of a request also walks that request's tree as in specvlm_tree_accept.  Arguments and
  * outputs are those of the two calls (amax_dev is written as well), plus
- *   counters_dev  device int32 [B]: arrival counters, ZERO-FILLED ONCE after allocation (every call
- *                 leaves them zero); calls that may run concurrently need separate counters.
+ *   counters_dev  device int32 [B * SPECVLM_COUNTER_STRIDE]: arrival counters, one per request, each on a
+ *                 128-byte line of its own (the rows of a request all add to its counter; counters of
+ *                 several requests on one line would queue up behind each other).  ZERO-FILLED ONCE
+ *                 after allocation (every call leaves them zero); calls that may run concurrently
+ *                 need separate counters.
  */
 int32_t specvlm_node_argmax_accept(int32_t dtype, int32_t B, int32_t N_max, int32_t V, int32_t path_cap,
                                    const void *logits_dev, int64_t stride_b, int64_t stride_n,
@@ -385,8 +389,9 @@ int32_t specvlm_draft_topk(int32_t dtype, int32_t B, int32_t W, int32_t V, int32
  * specvlm_draft_topk followed by specvlm_draft_select over the level's W*K new candidates
  * (score = score_out[b, 0 .. W*K), same M / index_base / sel_* / count_out meaning), as one
  * launch: the workgroup that finishes a request's last row makes the selection.  W*K <= 1024.
- *   counters_dev   device int32 [B], ZERO-FILLED ONCE after allocation (every call leaves it
- *                  zero); calls that may run concurrently need separate counters
+ *   counters_dev   device int32 [B * SPECVLM_COUNTER_STRIDE] (request b's counter is word
+ *                  b * SPECVLM_COUNTER_STRIDE), ZERO-FILLED ONCE after allocation (every call leaves
+ *                  it zero); calls that may run concurrently need separate counters
  */
 int32_t specvlm_draft_topk_select(int32_t dtype, int32_t B, int32_t W, int32_t V, int32_t K,
                                   const void *logits_dev, int64_t stride_b, int64_t stride_w,

@@ -145,6 +145,19 @@ def _dev_i32(t, name):
     return t
 
 
+COUNTER_STRIDE = 32                 # SPECVLM_COUNTER_STRIDE: int32 words between two requests' arrival counters
+
+
+def _request_counters(counters, B, dev):
+    """The per-request arrival counters of the fused calls: allocated (zeroed) when omitted, else checked."""
+    if counters is None:
+        return torch.zeros(B * COUNTER_STRIDE, dtype=torch.int32, device=dev)
+    _dev_i32(counters, "counters")
+    if counters.numel() < B * COUNTER_STRIDE:
+        raise ValueError(f"counters must hold B * COUNTER_STRIDE = {B * COUNTER_STRIDE} int32 words")
+    return counters
+
+
 def make_attn_desc(q, k_cache, out=None, *, block_table=None, softmax_scale=0.0, num_splits=0) -> AttnDesc:
     """Fill a specvlm_attn_desc from tensor shapes and strides.
 
@@ -383,8 +396,8 @@ def specvlm_draft_topk_select(logits, K, M, *, cum=None, parent_idx=None, score_
                               parent_out=None, lse_out=None, index_base=0, sel_out=None, sel_score_out=None,
                               count_out=None, counters=None, stream=None):
     """specvlm_draft_topk and the selection of the M best of the level's W*K new candidates in one launch.
-    `counters` is an int32 [B] device tensor, zero-filled once (allocated here when omitted).
-    Returns (score_out, token_out, parent_out, sel_out, sel_score_out, count_out)."""
+    `counters` is an int32 [B * COUNTER_STRIDE] device tensor, zero-filled once (allocated here when
+    omitted).  Returns (score_out, token_out, parent_out, sel_out, sel_score_out, count_out)."""
     B, W, V = logits.shape
     dev = logits.device
     if logits.stride(2) != 1:
@@ -407,8 +420,7 @@ def specvlm_draft_topk_select(logits, K, M, *, cum=None, parent_idx=None, score_
         sel_score_out = torch.empty((B, M), dtype=torch.float32, device=dev)
     if count_out is None:
         count_out = torch.empty(B, dtype=torch.int32, device=dev)
-    if counters is None:
-        counters = torch.zeros(B, dtype=torch.int32, device=dev)
+    counters = _request_counters(counters, B, dev)
     rc = lib().specvlm_draft_topk_select(
         _dtype_code(logits), B, W, V, K, _ptr(logits), logits.stride(0), logits.stride(1),
         _ptr(_dev_f32(cum, "cum")), 0 if cum is None else cum.stride(0),
@@ -526,8 +538,9 @@ def specvlm_visual_prune(x, keep, *, out=None, err_flag=None, stream=None):
 
 def specvlm_node_argmax_accept(logits, parent, draft_tok, *, num_nodes=None, path_cap=8, counters=None, amax=None,
                                err_flag=None, out=None, stream=None):
-    """specvlm_node_argmax + specvlm_tree_accept in one launch.  `counters` is an int32 [B] device tensor,
-    zero-filled once (allocated here when omitted).  Returns (amax, accept_len, path, bonus_tok, committed_tok)."""
+    """specvlm_node_argmax + specvlm_tree_accept in one launch.  `counters` is an int32
+    [B * COUNTER_STRIDE] device tensor, zero-filled once (allocated here when omitted).
+    Returns (amax, accept_len, path, bonus_tok, committed_tok)."""
     B, N_max, V = logits.shape
     dev = logits.device
     if logits.stride(2) != 1:
@@ -542,8 +555,7 @@ def specvlm_node_argmax_accept(logits, parent, draft_tok, *, num_nodes=None, pat
         committed = torch.empty((B, path_cap), dtype=torch.int32, device=dev)
     if amax is None:
         amax = torch.empty((B, N_max), dtype=torch.int32, device=dev)
-    if counters is None:
-        counters = torch.zeros(B, dtype=torch.int32, device=dev)
+    counters = _request_counters(counters, B, dev)
     rc = lib().specvlm_node_argmax_accept(
         _dtype_code(logits), B, N_max, V, path_cap, _ptr(logits), logits.stride(0), logits.stride(1),
         _ptr(_dev_i32(num_nodes, "num_nodes")), _ptr(_dev_i32(parent, "parent")),

@@ -50,7 +50,7 @@ using namespace specvlm;
 
 extern "C" {
 
-int32_t specvlm_version(void) { return 201; }
+int32_t specvlm_version(void) { return 300; }
 
 int32_t specvlm_last_hip_error(void) { return g_last_hip_error; }
 

@@ -337,7 +337,7 @@ struct SelArgs {
     int32_t* sel_out;
     float* sel_score_out;
     int32_t* count_out;
-    int32_t* counters;            // [B] tickets, zero between calls
+    int32_t* counters;            // [B * SPECVLM_COUNTER_STRIDE] tickets, zero between calls
 };
 
 template <typename T, int NS, bool SEL>
@@ -585,7 +585,7 @@ __global__ __launch_bounds__(kThreadsDT) void draft_topk_kernel(
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's score stores have been acknowledged
         __syncthreads();
         if (tid == 0) {
-            int32_t* cnt = sel.counters + b;
+            int32_t* cnt = sel.counters + b * SPECVLM_COUNTER_STRIDE;
             const int ticket = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const int last = ticket == nrows - 1;
             if (last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -25,6 +25,15 @@ __device__ __forceinline__ void take_better(ValIdx& a, float v, int i) {
     }
 }
 
+// The same when i is known to be greater than every index taken so far (a thread scans its entries
+// in increasing order): equal values keep the earlier index, so only "greater" replaces.
+__device__ __forceinline__ void take_later(ValIdx& a, float v, int i) {
+    if (v > a.v) {
+        a.v = v;
+        a.i = i;
+    }
+}
+
 template <typename T>
 struct Elem;
 template <>
@@ -83,9 +92,10 @@ __global__ __launch_bounds__(1024) void node_argmax_kernel(int N_max, int V, con
             if (tid == 0) {
                 __hip_atomic_store(amax + row, result, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // the store has been acknowledged
-                const int ticket = __hip_atomic_fetch_add(acc.counters + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                int32_t* cnt = acc.counters + b * SPECVLM_COUNTER_STRIDE;     // a cache line per request
+                const int ticket = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 const int last = ticket == N_max - 1;
-                if (last) __hip_atomic_store(acc.counters + b, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 s_last = last;
             }
             __syncthreads();
@@ -105,16 +115,30 @@ __global__ __launch_bounds__(1024) void node_argmax_kernel(int N_max, int V, con
     // scalar head up to the first 16-byte boundary, vector body, scalar tail
     int head = static_cast<int>(((16u - (reinterpret_cast<uintptr_t>(p) & 15u)) & 15u) / sizeof(T));
     head = min(head, V);
-    for (int v = tid; v < head; v += blockDim.x) take_better(best, Elem<T>::one(p + v), v);
+    // (every thread meets its entries in increasing index order: head, vector body, tail)
+    for (int v = tid; v < head; v += blockDim.x) take_later(best, Elem<T>::one(p + v), v);
     const int nvec = (V - head) / VEC;
     const uint4* pv = reinterpret_cast<const uint4*>(p + head);
-    for (int c = tid; c < nvec; c += blockDim.x) {
-        uint4 w = pv[c];
-        const int base = head + c * VEC;
+    // four 16-byte loads per thread are requested before the first is looked at (a row of 32000 bf16
+    // logits is four per thread: one memory round trip instead of four in a row)
+    for (int c0 = tid; c0 < nvec; c0 += 4 * blockDim.x) {
+        uint4 w[4];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) take_better(best, Elem<T>::at(w, e), base + e);
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * blockDim.x;
+            if (c < nvec) w[u] = pv[c];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * blockDim.x;
+            if (c < nvec) {
+                const int base = head + c * VEC;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) take_later(best, Elem<T>::at(w[u], e), base + e);
+            }
+        }
     }
-    for (int v = head + nvec * VEC + tid; v < V; v += blockDim.x) take_better(best, Elem<T>::one(p + v), v);
+    for (int v = head + nvec * VEC + tid; v < V; v += blockDim.x) take_later(best, Elem<T>::one(p + v), v);
 
     // wavefront (64 lanes) reduction, then across the 16 wavefronts through LDS
 #pragma unroll

@@ -126,3 +126,10 @@ def test_attention_kernels_spill_nothing():
             assert u["vgprs"] <= 128 and u["lds"] <= 80 * 1024, (name, u)
         else:
             assert u["lds"] <= 160 * 1024, (name, u)
+
+
+def test_binding_constants_are_the_headers():
+    import re
+    from paper_2509_11815_amd import binding
+    text = open(os.path.join(ROOT, "include", "specvlm.h")).read()
+    assert int(re.search(r"#define SPECVLM_COUNTER_STRIDE (\d+)", text).group(1)) == binding.COUNTER_STRIDE

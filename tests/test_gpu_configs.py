@@ -181,7 +181,7 @@ def test_whole_step_graph_replay_c3(sv, oracle):
     desc = sv.binding.make_attn_desc(q[0], k[0], out[0])
     workspace = torch.zeros(max(sv.specvlm_tree_verify_attn_workspace_bytes(desc), 256), dtype=torch.uint8, device="cuda")
     err = torch.zeros(1, dtype=torch.int32, device="cuda")
-    counters = torch.zeros(cfg.B, dtype=torch.int32, device="cuda")
+    counters = torch.zeros(cfg.B * sv.binding.COUNTER_STRIDE, dtype=torch.int32, device="cuda")
     amax = torch.zeros((cfg.B, cfg.N), dtype=torch.int32, device="cuda")
     acc = (torch.zeros(cfg.B, dtype=torch.int32, device="cuda"), torch.zeros((cfg.B, cap), dtype=torch.int32, device="cuda"),
            torch.zeros(cfg.B, dtype=torch.int32, device="cuda"), torch.zeros((cfg.B, cap), dtype=torch.int32, device="cuda"))

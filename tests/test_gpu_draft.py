@@ -157,7 +157,7 @@ def test_topk_select_in_one_launch_equals_the_two_calls(sv, oracle, dtype, V):
     cum = (-rng.random((B, Wd)) * 3).astype(np.float32)
     cum[:, 4] = cum[:, 1]
     par = rng.integers(0, 500, size=(B, Wd)).astype(np.int32)
-    counters = torch.zeros(B, dtype=torch.int32, device="cuda")
+    counters = torch.zeros(B * sv.binding.COUNTER_STRIDE, dtype=torch.int32, device="cuda")
     lg, cm, pr = to_dev(logits), _f32(cum), i32(par)
     score, token, parent = sv.specvlm_draft_topk(lg, K, cum=cm, parent_idx=pr)
     for M in (10, 100):
@@ -191,7 +191,7 @@ def _grow_on_gpu(sv, level_logits, root_token, K, width, N_max, fused=False):
     token = torch.zeros((B, C), dtype=torch.int32, device="cuda")
     parent = torch.full((B, C), -1, dtype=torch.int32, device="cuda")
     base, count, sels = 0, 0, []
-    counters = torch.zeros(B, dtype=torch.int32, device="cuda")
+    counters = torch.zeros(B * sv.binding.COUNTER_STRIDE, dtype=torch.int32, device="cuda")
     sel = sel_score = None
     for d, lg in enumerate(level_logits):
         rows = lg.shape[1]

@@ -197,7 +197,7 @@ def test_fused_argmax_accept_matches_oracle(sv, oracle, dtype):
     from gpu_util import i32, to_dev
     rng = np.random.default_rng(17)
     B, N, V, cap = 5, 60, 1000, 8
-    counters = torch.zeros(B, dtype=torch.int32, device="cuda")
+    counters = torch.zeros(B * sv.binding.COUNTER_STRIDE, dtype=torch.int32, device="cuda")
     err = torch.zeros(1, dtype=torch.int32, device="cuda")
     for rep in range(3):
         trees = [W.eagle_tree(rng, N, 6, 10) for _ in range(B)]
@@ -223,6 +223,10 @@ def test_fused_argmax_accept_matches_oracle(sv, oracle, dtype):
                                                      counters=counters, err_flag=err)
     assert int(err.item()) & 1 and int(m[1].item()) == 0 and path[1].tolist() == [0] + [-1] * (cap - 1)
     assert int(counters.abs().sum().item()) == 0
+    # one counter per request, each on a cache line of its own: a [B] tensor is too small and is refused
+    with pytest.raises(ValueError):
+        sv.specvlm_node_argmax_accept(to_dev(logits), i32(parent), i32(tok), path_cap=cap,
+                                      counters=torch.zeros(B, dtype=torch.int32, device="cuda"), err_flag=err)
 
 
 # ------------------------------------------------------------------ offsets that need 64 bits
